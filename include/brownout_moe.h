@@ -1,0 +1,183 @@
+/*
+ * brownout_moe.h -- C ABI of the MI355X (gfx950) BrownoutMoE layer library.
+ *
+ * One MoE layer's forward pass with the brownout mechanism of BrownoutServe
+ * (arXiv 2507.17133): gate affinities and TopK weights (section "Architecture
+ * of BrownoutMoE"), the brownout decision of Algorithm 1 (section "Brownout
+ * Approach"), token rows grouped per execution unit, the expert FFNs (original,
+ * united, shared) and the weighted sum of the layer equation.
+ *
+ * Conventions
+ *   - Every data pointer is a DEVICE pointer owned by the caller; the library
+ *     never allocates or frees device memory.  moe_config / moe_ffn_weights /
+ *     moe_route_out structs themselves live in HOST memory.
+ *   - All work is enqueued on the HIP stream passed as `stream` (a hipStream_t
+ *     cast to void*, NULL = default stream); no call synchronises with the host
+ *     (moe_profile_collect excepted).  Per-expert counts stay on the device.
+ *   - Arguments are validated on the host before any launch; on error nothing
+ *     has been enqueued.  Every function returns a moe_status.
+ *   - Activations and FFN weights are bf16 (round-to-nearest-even), gate
+ *     weights fp32; FFN accumulation is fp32.  All matrices are row-major and
+ *     dense.  Pointers must be 16-byte aligned.
+ *   - Symbols: T tokens, d = d_model, F = d_ff, m = n_experts, K = top_k,
+ *     way = experts per united-expert group (the paper's k), G = ceil(m/way),
+ *     N_s = n_shared, U = m + G + N_s execution units, numbered
+ *     0..m-1 original experts, m..m+G-1 united experts, m+G.. shared experts.
+ *   - Limits: d and F (and d_ff_shared) multiples of 64; m <= 256; K <= min(m,32);
+ *     N_s <= 8; T*(K+N_s) <= 2^30.
+ */
+#ifndef BROWNOUT_MOE_H
+#define BROWNOUT_MOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t moe_status;
+#define MOE_OK 0
+#define MOE_ERR_INVALID_ARG (-1) /* NULL required pointer, value out of range            */
+#define MOE_ERR_SHAPE (-2)       /* a dimension violates the limits above                */
+#define MOE_ERR_ALIGNMENT (-3)   /* a pointer is not 16-byte aligned                     */
+#define MOE_ERR_WORKSPACE (-4)   /* workspace NULL or smaller than moe_workspace_size    */
+#define MOE_ERR_UNSUPPORTED (-5) /* valid request this build does not implement          */
+#define MOE_ERR_HIP (-6)         /* a HIP runtime call failed (see moe_last_hip_error)   */
+
+typedef struct moe_config {
+    int32_t d_model;      /* d                                                              */
+    int32_t d_ff;         /* F of original AND united experts (a united expert has the      */
+                          /* parameter size of one original expert: Introduction)           */
+    int32_t n_experts;    /* m  (United Expert Model)                                       */
+    int32_t top_k;        /* K  (TopK(.,K) in the g equation)                               */
+    int32_t way;          /* experts per group; G = ceil(m/way) united experts              */
+    int32_t n_shared;     /* N_s shared experts of the layer equation, 0 if none            */
+    int32_t d_ff_shared;  /* F of a shared expert (ignored if n_shared == 0)                */
+    int32_t score_fn;     /* 0: g = softmax over the K winners (the g equation);            */
+                          /* 1: sigmoid(s) renormalised over the K winners                  */
+    int32_t add_residual; /* 1: output includes the "x_t +" term of the layer equation      */
+    int32_t reserved;     /* must be 0                                                      */
+} moe_config;
+
+/* n SwiGLU experts, FFN(x) = W2 (silu(W1 x) * (W3 x)):
+ *   w1, w3: [n][F][d] bf16     w2: [n][d][F] bf16
+ * (each matrix stored [out_features][in_features]). */
+typedef struct moe_ffn_weights {
+    const void *w1, *w3, *w2;
+} moe_ffn_weights;
+
+/* Routing artefacts.  In moe_route every field may be NULL (not wanted).  A
+ * moe_route_out handed to moe_forward must have expert_unit, unit_cnt,
+ * unit_off, row_token, row_weight and token_rows set, as written by moe_route
+ * with the same config and T. */
+typedef struct moe_route_out {
+    int32_t *topk_idx;    /* [T][K]   experts by descending affinity, equal affinities: lower id first */
+    float *topk_w;        /* [T][K]   g of those experts                                                */
+    int32_t *expert_cnt;  /* [m]      cnt_i of Algorithm 1 (before brownout); sums to T*K               */
+    int32_t *expert_unit; /* [m]      unit serving expert i: i, m+g (united g), -1 (dropped)            */
+    uint8_t *expert_in_s1;/* [m]      1 if expert i is in S1                                            */
+    int32_t *unit_cnt;    /* [U]      rows of each execution unit                                       */
+    int32_t *unit_off;    /* [U+1]    exclusive prefix of unit_cnt                                      */
+    int32_t *row_token;   /* [T*(K+N_s)] token of each row; rows of a unit are contiguous, ascending    */
+                          /*          token; first unit_off[U] entries valid                            */
+    float *row_weight;    /* [T*(K+N_s)] weight of each row.  A token whose TopK holds several experts  */
+                          /*          delegated to one united expert has ONE row there, weight = sum    */
+                          /*          of their g (added in TopK order); shared rows have weight 1       */
+    int32_t *token_rows;  /* [T][K+N_s] row of TopK entry j (or -1: dropped / merged into an earlier    */
+                          /*          entry's row); entries K.. are the token's rows in the shared units*/
+    int32_t *n_rows;      /* [1]      = unit_off[U]                                                     */
+    uint8_t *near_tie;    /* [T]      1 if two neighbours among the K winners + best loser differ by    */
+                          /*          less than 1e-6 in the fp32 logits (a decision that rounding       */
+                          /*          order could flip)                                                 */
+} moe_route_out;
+
+const char *moe_status_string(moe_status s);
+/* Text of the last HIP error seen by this thread ("" if none). */
+const char *moe_last_hip_error(void);
+
+/* Bytes of device workspace moe_route / moe_forward / moe_build_united need for up
+ * to T_max tokens (or calibration tokens) with this config.  256-byte aligned base. */
+moe_status moe_workspace_size(const moe_config *cfg, int32_t T_max, size_t *bytes);
+
+/*
+ * United experts (section "United Expert Model").  The paper trains one student
+ * per group of `way` consecutive experts by distillation and does not give the
+ * recipe; this call writes the student's starting point, the element-wise mean
+ * of the group's parameters (sum in member order and one division in fp64,
+ * rounded once to bf16; the last group averages its actual members), into the
+ * caller's `united` tensors ([G][F][d], [G][F][d], [G][d][F]).  If calib_x
+ * ([n_calib][d] bf16) and loss_per_group ([G] fp32) are given it also evaluates
+ * the MSE equation of that section on the calibration tokens:
+ *   L^j = (1/k_j) sum_i ||H_u^j - H_o^{j*way+i}||^2,
+ * H = FFN outputs, squared norm summed over features and averaged over tokens.
+ * Errors: NULL experts/united pointers, n_calib < 0, workspace too small.
+ */
+moe_status moe_build_united(const moe_config *cfg, const moe_ffn_weights *experts,
+                            const moe_ffn_weights *united_out, const void *calib_x, int32_t n_calib,
+                            float *loss_per_group, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Gate + TopK + Algorithm 1 + row lists for T tokens x [T][d] bf16.
+ *   gate_w [m][d] fp32 (row i = centroid e_i), gate_bias [m] fp32 or NULL:
+ *   s_{i,t} = x_t . e_i (+ bias_i), accumulated to fp32 accuracy.
+ *   threshold in [0,1]: share of token->expert assignments that stays on
+ *   original experts (1 = zero-brownout).  Algorithm 1 is read so that it
+ *   reproduces the paper's worked examples: experts sorted by count descending
+ *   (equal counts: lower id first) join S1 while the count already covered is
+ *   < S*threshold (double product); the rest are S2.  S2 experts of a group
+ *   go to united expert floor(i/way) if at least two of them hold tokens, else
+ *   the single one serves itself; with use_full_brownout != 0 S2 is dropped.
+ * Errors: threshold outside [0,1] or NaN, top_k > n_experts, way < 1, T <= 0,
+ * NULL x / gate_w / out, misaligned pointers, workspace too small.
+ */
+moe_status moe_route(const moe_config *cfg, const void *x, int32_t T, const float *gate_w,
+                     const float *gate_bias, double threshold, int32_t use_full_brownout,
+                     const moe_route_out *out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * The layer equation:
+ *   out_t = [x_t] + sum_s FFN^(s)_s(x_t) + sum_i p_{i,t} FFN^(r)_i(x_t) + sum_i q_{i,t} FFN^(u)_{floor(i/way)}(x_t)
+ * out [T][d] bf16.  route == NULL: routing is computed internally exactly as
+ * moe_route does (gate_w required); otherwise the given rows are used and
+ * gate_w / gate_bias / threshold / use_full_brownout are ignored.
+ * `united` may be NULL only if no token can reach a united expert
+ * (threshold == 1 or use_full_brownout); `shared` must be set iff n_shared > 0.
+ * Intermediate activations are bf16, sums fp32; the sum over a token's rows
+ * is taken in TopK order, shared experts first (deterministic, no atomics).
+ */
+moe_status moe_forward(const moe_config *cfg, const void *x, int32_t T, const float *gate_w,
+                       const float *gate_bias, const moe_ffn_weights *experts, const moe_ffn_weights *united,
+                       const moe_ffn_weights *shared, double threshold, int32_t use_full_brownout,
+                       const moe_route_out *route, void *out, void *workspace, size_t workspace_bytes,
+                       void *stream);
+
+/*
+ * Per-kernel timing for benchmarks.  moe_profile_enable takes a bit mask of
+ * stages (bit MOE_STAGE_x; 0 switches profiling off).  While a stage is
+ * enabled, moe_route / moe_forward / moe_build_united bracket that stage's
+ * kernel with two HIP events on the caller's stream (up to 4096 calls are
+ * kept, later ones are not recorded).  moe_profile_collect waits for the
+ * recorded events, adds up the elapsed milliseconds and the number of
+ * launches per stage and clears the record.  Process-wide state; not
+ * thread-safe.
+ */
+enum {
+    MOE_STAGE_PREP = 0,   /* clear counters, split gate weights                */
+    MOE_STAGE_GATE = 1,   /* affinities, TopK, weights, expert counts          */
+    MOE_STAGE_COUNT = 2,  /* Algorithm 1 + rows per unit and token block       */
+    MOE_STAGE_SCAN = 3,   /* offsets                                           */
+    MOE_STAGE_SCATTER = 4,/* row lists                                         */
+    MOE_STAGE_TILES = 5,  /* GEMM tile table                                   */
+    MOE_STAGE_GEMM1 = 6,  /* rows x [W1|W3] + SwiGLU                           */
+    MOE_STAGE_GEMM2 = 7,  /* H x W2, row weights                               */
+    MOE_STAGE_COMBINE = 8,/* weighted sum per token                            */
+    MOE_N_STAGES = 9
+};
+moe_status moe_profile_enable(int32_t stage_mask);
+moe_status moe_profile_collect(double *total_ms /*[MOE_N_STAGES]*/, int64_t *launches /*[MOE_N_STAGES]*/);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BROWNOUT_MOE_H */

@@ -218,3 +218,28 @@ def route(x, gate_w, gate_bias, K, way, threshold, use_full_brownout=False, scor
     unit, in_s1 = brownout_decide(cnt, way, threshold, use_full_brownout)
     rows = build_rows(idx, w, m, way, n_shared, unit)
     return Route(s64, s32, idx, w, margin, cnt, unit, in_s1, rows)
+
+
+def forward_tokens_lazy(x_rows, topk_idx_rows, topk_w_rows, unit, m, get_weights, n_shared=0, add_residual=False):
+    """The layer equation for a few tokens when the weights are too large to hold as one float
+    array: x_rows [n,d], topk_idx_rows / topk_w_rows [n,K] are the sampled tokens' data and
+    get_weights(kind, index) returns one FFN's (w1 [F,d], w3 [F,d], w2 [d,F]) as float arrays,
+    kind in {"expert", "united", "shared"}.  Each term is one call of ffn() on one row; the sum
+    over terms is taken in double.  Returns [n,d] double."""
+    x_rows = _f32(x_rows)
+    n, d = x_rows.shape
+    K = topk_idx_rows.shape[1]
+    out = np.zeros((n, d), np.float64)
+    for q in range(n):
+        xr = x_rows[q:q + 1]
+        if add_residual:
+            out[q] += xr[0].astype(np.float64)
+        for s in range(n_shared):
+            out[q] += ffn(xr, *get_weights("shared", s))[0]
+        for j in range(K):
+            u = int(unit[int(topk_idx_rows[q, j])])
+            if u < 0:
+                continue
+            w = get_weights("expert", u) if u < m else get_weights("united", u - m)
+            out[q] += float(topk_w_rows[q, j]) * ffn(xr, *w)[0]
+    return out

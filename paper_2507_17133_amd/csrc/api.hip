@@ -1,0 +1,402 @@
+// C ABI of libbrownout_moe.so: argument validation, workspace carving, kernel sequencing, profiling.
+#include "internal.h"
+
+#include <cmath>
+#include <cstring>
+#include <string>
+#include <vector>
+
+namespace bmoe {
+
+static thread_local std::string g_hip_error;
+
+static moe_status hip_fail(hipError_t e, const char* where)
+{
+    g_hip_error = std::string(where) + ": " + hipGetErrorString(e);
+    (void)hipGetLastError();
+    return MOE_ERR_HIP;
+}
+
+Dims make_dims(const moe_config& c, int T)
+{
+    Dims D;
+    D.T = T; D.d = c.d_model; D.F = c.d_ff; D.m = c.n_experts; D.K = c.top_k; D.way = c.way;
+    D.G = ceil_div(c.n_experts, c.way);
+    D.Ns = c.n_shared; D.Fs = c.n_shared > 0 ? c.d_ff_shared : 0;
+    D.U = D.m + D.G + D.Ns;
+    D.slots = D.K + D.Ns;
+    D.m_pad = ceil_div(D.m, 16) * 16;
+    D.Fmax = D.F > D.Fs ? D.F : D.Fs;
+    D.score_fn = c.score_fn; D.add_residual = c.add_residual;
+    D.row_cap = (int64_t)T * D.slots;
+    D.n_seg = ceil_div(T, kSegTokens);
+    D.tile_cap = (int)(D.row_cap / kMinTileRows) + D.U;
+    return D;
+}
+
+Workspace carve_workspace(const Dims& D)
+{
+    Workspace W;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
+    W.topk_idx = take((size_t)D.T * D.K * 4);
+    W.topk_w = take((size_t)D.T * D.K * 4);
+    W.expert_cnt = take((size_t)D.m * 4);
+    W.expert_unit = take((size_t)D.m * 4);
+    W.expert_in_s1 = take((size_t)D.m);
+    W.unit_cnt = take((size_t)D.U * 4);
+    W.unit_off = take((size_t)(D.U + 1) * 4);
+    W.row_token = take((size_t)D.row_cap * 4);
+    W.row_weight = take((size_t)D.row_cap * 4);
+    W.token_rows = take((size_t)D.row_cap * 4);
+    W.n_rows = take(4);
+    W.near_tie = take((size_t)D.T);
+    W.gate_split = take((size_t)3 * D.m_pad * D.d * 2);
+    W.seg_cnt = take((size_t)D.n_seg * D.U * 4);
+    W.seg_off = take((size_t)D.n_seg * D.U * 4);
+    W.tiles0 = take(16 + (size_t)D.tile_cap * 16);
+    W.tiles1 = take(16 + (size_t)D.tile_cap * 16);
+    W.h_rows = D.row_cap;
+    W.y_rows = D.row_cap > 2 * (int64_t)D.T ? D.row_cap : 2 * (int64_t)D.T;
+    W.H = take((size_t)W.h_rows * D.Fmax * 2);
+    W.Y = take((size_t)W.y_rows * D.d * 2);
+    W.ones = take((size_t)D.T * 4);
+    W.total = o;
+    return W;
+}
+
+static moe_status check_config(const moe_config* c)
+{
+    if (!c) return MOE_ERR_INVALID_ARG;
+    if (c->reserved != 0) return MOE_ERR_INVALID_ARG;
+    if (c->n_experts < 1 || c->top_k < 1 || c->way < 1 || c->n_shared < 0) return MOE_ERR_INVALID_ARG;
+    if (c->top_k > c->n_experts) return MOE_ERR_INVALID_ARG;
+    if (c->score_fn != 0 && c->score_fn != 1) return MOE_ERR_INVALID_ARG;
+    if (c->add_residual != 0 && c->add_residual != 1) return MOE_ERR_INVALID_ARG;
+    if (c->d_model <= 0 || c->d_ff <= 0 || c->d_model % 64 || c->d_ff % 64) return MOE_ERR_SHAPE;
+    if (c->n_shared > 0 && (c->d_ff_shared <= 0 || c->d_ff_shared % 64)) return MOE_ERR_SHAPE;
+    if (c->n_experts > kMaxExperts || c->top_k > kMaxTopK || c->n_shared > kMaxShared) return MOE_ERR_SHAPE;
+    return MOE_OK;
+}
+
+static moe_status check_T(const moe_config* c, int32_t T)
+{
+    if (T <= 0) return MOE_ERR_INVALID_ARG;
+    if ((int64_t)T * (c->top_k + c->n_shared) > ((int64_t)1 << 30)) return MOE_ERR_SHAPE;
+    return MOE_OK;
+}
+
+static bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+static moe_status check_weights(const moe_ffn_weights* w)
+{
+    if (!w || !w->w1 || !w->w3 || !w->w2) return MOE_ERR_INVALID_ARG;
+    if (misaligned(w->w1) || misaligned(w->w3) || misaligned(w->w2)) return MOE_ERR_ALIGNMENT;
+    return MOE_OK;
+}
+
+static FfnWeights to_ffn(const moe_ffn_weights* w)
+{
+    FfnWeights f{nullptr, nullptr, nullptr};
+    if (w) {
+        f.w1 = static_cast<const bf16_t*>(w->w1);
+        f.w3 = static_cast<const bf16_t*>(w->w3);
+        f.w2 = static_cast<const bf16_t*>(w->w2);
+    }
+    return f;
+}
+
+template <typename Tp>
+static Tp* at(void* ws, size_t off) { return reinterpret_cast<Tp*>(static_cast<char*>(ws) + off); }
+
+static RouteBufs resolve_route(const moe_route_out* o, void* ws, const Workspace& W)
+{
+    RouteBufs R;
+    R.topk_idx = (o && o->topk_idx) ? o->topk_idx : at<int32_t>(ws, W.topk_idx);
+    R.topk_w = (o && o->topk_w) ? o->topk_w : at<float>(ws, W.topk_w);
+    R.expert_cnt = (o && o->expert_cnt) ? o->expert_cnt : at<int32_t>(ws, W.expert_cnt);
+    R.expert_unit = (o && o->expert_unit) ? o->expert_unit : at<int32_t>(ws, W.expert_unit);
+    R.expert_in_s1 = (o && o->expert_in_s1) ? o->expert_in_s1 : at<uint8_t>(ws, W.expert_in_s1);
+    R.unit_cnt = (o && o->unit_cnt) ? o->unit_cnt : at<int32_t>(ws, W.unit_cnt);
+    R.unit_off = (o && o->unit_off) ? o->unit_off : at<int32_t>(ws, W.unit_off);
+    R.row_token = (o && o->row_token) ? o->row_token : at<int32_t>(ws, W.row_token);
+    R.row_weight = (o && o->row_weight) ? o->row_weight : at<float>(ws, W.row_weight);
+    R.token_rows = (o && o->token_rows) ? o->token_rows : at<int32_t>(ws, W.token_rows);
+    R.n_rows = (o && o->n_rows) ? o->n_rows : at<int32_t>(ws, W.n_rows);
+    R.near_tie = (o && o->near_tie) ? o->near_tie : at<uint8_t>(ws, W.near_tie);
+    return R;
+}
+
+static moe_status check_route_ptr_alignment(const moe_route_out* o)
+{
+    const void* ps[] = {o->topk_idx, o->topk_w, o->expert_cnt, o->expert_unit, o->unit_cnt, o->unit_off,
+                        o->row_token, o->row_weight, o->token_rows, o->n_rows};
+    for (const void* p : ps)
+        if (p && (reinterpret_cast<uintptr_t>(p) & 3u)) return MOE_ERR_ALIGNMENT;
+    return MOE_OK;
+}
+
+// ---------------------------------------------------------------- profiling
+struct ProfRecord { int stage; hipEvent_t a, b; };
+static unsigned g_prof_mask = 0;
+static std::vector<ProfRecord> g_prof_records;
+static std::vector<hipEvent_t> g_prof_pool;
+static hipEvent_t g_prof_open[MOE_N_STAGES];
+static bool g_prof_is_open[MOE_N_STAGES] = {false};
+constexpr size_t kProfMaxRecords = 4096 * MOE_N_STAGES;
+
+static hipEvent_t prof_event()
+{
+    if (!g_prof_pool.empty()) {
+        hipEvent_t e = g_prof_pool.back();
+        g_prof_pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+void prof_begin(int stage, hipStream_t s)
+{
+    if (!(g_prof_mask & (1u << stage)) || g_prof_records.size() >= kProfMaxRecords) return;
+    hipEvent_t e = prof_event();
+    if (!e) return;
+    (void)hipEventRecord(e, s);
+    g_prof_open[stage] = e;
+    g_prof_is_open[stage] = true;
+}
+
+void prof_end(int stage, hipStream_t s)
+{
+    if (!g_prof_is_open[stage]) return;
+    g_prof_is_open[stage] = false;
+    hipEvent_t e = prof_event();
+    if (!e) { g_prof_pool.push_back(g_prof_open[stage]); return; }
+    (void)hipEventRecord(e, s);
+    g_prof_records.push_back(ProfRecord{stage, g_prof_open[stage], e});
+}
+
+}  // namespace bmoe
+
+using namespace bmoe;
+
+extern "C" {
+
+const char* moe_status_string(moe_status s)
+{
+    switch (s) {
+        case MOE_OK: return "ok";
+        case MOE_ERR_INVALID_ARG: return "invalid argument";
+        case MOE_ERR_SHAPE: return "unsupported shape";
+        case MOE_ERR_ALIGNMENT: return "misaligned pointer";
+        case MOE_ERR_WORKSPACE: return "workspace missing or too small";
+        case MOE_ERR_UNSUPPORTED: return "not implemented";
+        case MOE_ERR_HIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+const char* moe_last_hip_error(void) { return g_hip_error.c_str(); }
+
+moe_status moe_workspace_size(const moe_config* cfg, int32_t T_max, size_t* bytes)
+{
+    moe_status st = check_config(cfg);
+    if (st != MOE_OK) return st;
+    if (!bytes) return MOE_ERR_INVALID_ARG;
+    st = check_T(cfg, T_max);
+    if (st != MOE_OK) return st;
+    *bytes = carve_workspace(make_dims(*cfg, T_max)).total;
+    return MOE_OK;
+}
+
+moe_status moe_route(const moe_config* cfg, const void* x, int32_t T, const float* gate_w, const float* gate_bias,
+                     double threshold, int32_t use_full_brownout, const moe_route_out* out, void* workspace,
+                     size_t workspace_bytes, void* stream)
+{
+    moe_status st = check_config(cfg);
+    if (st != MOE_OK) return st;
+    st = check_T(cfg, T);
+    if (st != MOE_OK) return st;
+    if (!x || !gate_w || !out) return MOE_ERR_INVALID_ARG;
+    if (!(threshold >= 0.0 && threshold <= 1.0)) return MOE_ERR_INVALID_ARG;
+    if (misaligned(x) || misaligned(gate_w) || (gate_bias && (reinterpret_cast<uintptr_t>(gate_bias) & 3u)))
+        return MOE_ERR_ALIGNMENT;
+    st = check_route_ptr_alignment(out);
+    if (st != MOE_OK) return st;
+    const Dims D = make_dims(*cfg, T);
+    const Workspace W = carve_workspace(D);
+    if (!workspace || workspace_bytes < W.total) return MOE_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return MOE_ERR_ALIGNMENT;
+    const RouteBufs R = resolve_route(out, workspace, W);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = launch_route(D, static_cast<const bf16_t*>(x), gate_w, gate_bias, threshold,
+                                use_full_brownout ? 1 : 0, R, at<bf16_t>(workspace, W.gate_split),
+                                at<int32_t>(workspace, W.seg_cnt), at<int32_t>(workspace, W.seg_off), s);
+    if (e != hipSuccess) return hip_fail(e, "moe_route");
+    return MOE_OK;
+}
+
+moe_status moe_forward(const moe_config* cfg, const void* x, int32_t T, const float* gate_w, const float* gate_bias,
+                       const moe_ffn_weights* experts, const moe_ffn_weights* united, const moe_ffn_weights* shared,
+                       double threshold, int32_t use_full_brownout, const moe_route_out* route, void* out,
+                       void* workspace, size_t workspace_bytes, void* stream)
+{
+    moe_status st = check_config(cfg);
+    if (st != MOE_OK) return st;
+    st = check_T(cfg, T);
+    if (st != MOE_OK) return st;
+    if (!x || !out) return MOE_ERR_INVALID_ARG;
+    if (misaligned(x) || misaligned(out)) return MOE_ERR_ALIGNMENT;
+    st = check_weights(experts);
+    if (st != MOE_OK) return st;
+    if (cfg->n_shared > 0) {
+        st = check_weights(shared);
+        if (st != MOE_OK) return st;
+    } else if (shared) {
+        return MOE_ERR_INVALID_ARG;
+    }
+    if (united) {
+        st = check_weights(united);
+        if (st != MOE_OK) return st;
+    }
+    if (!route) {
+        if (!gate_w) return MOE_ERR_INVALID_ARG;
+        if (!(threshold >= 0.0 && threshold <= 1.0)) return MOE_ERR_INVALID_ARG;
+        if (misaligned(gate_w) || (gate_bias && (reinterpret_cast<uintptr_t>(gate_bias) & 3u)))
+            return MOE_ERR_ALIGNMENT;
+        if (!united && threshold < 1.0 && !use_full_brownout) return MOE_ERR_INVALID_ARG;
+    } else {
+        if (!route->expert_unit || !route->unit_cnt || !route->unit_off || !route->row_token || !route->row_weight ||
+            !route->token_rows)
+            return MOE_ERR_INVALID_ARG;
+        st = check_route_ptr_alignment(route);
+        if (st != MOE_OK) return st;
+    }
+    const Dims D = make_dims(*cfg, T);
+    const Workspace W = carve_workspace(D);
+    if (!workspace || workspace_bytes < W.total) return MOE_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return MOE_ERR_ALIGNMENT;
+    const RouteBufs R = resolve_route(route, workspace, W);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bf16_t* xb = static_cast<const bf16_t*>(x);
+    hipError_t e;
+    if (!route) {
+        e = launch_route(D, xb, gate_w, gate_bias, threshold, use_full_brownout ? 1 : 0, R,
+                         at<bf16_t>(workspace, W.gate_split), at<int32_t>(workspace, W.seg_cnt),
+                         at<int32_t>(workspace, W.seg_off), s);
+        if (e != hipSuccess) return hip_fail(e, "moe_forward/route");
+    }
+    const FfnWeights fe = to_ffn(experts), fu = to_ffn(united), fs = to_ffn(shared);
+    bf16_t* H = at<bf16_t>(workspace, W.H);
+    bf16_t* Y = at<bf16_t>(workspace, W.Y);
+    const int64_t rows_per_expert = (int64_t)T * D.K / D.m;
+    if (D.Ns > 0 && D.Fs != D.F) {
+        e = launch_ffn(D, 0, D.m + D.G, D.F, rows_per_expert, xb, R.row_token, R.unit_cnt, R.unit_off, R.row_weight,
+                       fe, fu, fs, at<int32_t>(workspace, W.tiles0), H, Y, s);
+        if (e != hipSuccess) return hip_fail(e, "moe_forward/ffn");
+        e = launch_ffn(D, D.m + D.G, D.U, D.Fs, T, xb, R.row_token, R.unit_cnt, R.unit_off, R.row_weight, fe, fu, fs,
+                       at<int32_t>(workspace, W.tiles1), H, Y, s);
+        if (e != hipSuccess) return hip_fail(e, "moe_forward/ffn_shared");
+    } else {
+        e = launch_ffn(D, 0, D.U, D.F, rows_per_expert, xb, R.row_token, R.unit_cnt, R.unit_off, R.row_weight, fe, fu,
+                       fs, at<int32_t>(workspace, W.tiles0), H, Y, s);
+        if (e != hipSuccess) return hip_fail(e, "moe_forward/ffn");
+    }
+    e = launch_combine(D, xb, Y, R.token_rows, static_cast<bf16_t*>(out), s);
+    if (e != hipSuccess) return hip_fail(e, "moe_forward/combine");
+    return MOE_OK;
+}
+
+moe_status moe_build_united(const moe_config* cfg, const moe_ffn_weights* experts, const moe_ffn_weights* united_out,
+                            const void* calib_x, int32_t n_calib, float* loss_per_group, void* workspace,
+                            size_t workspace_bytes, void* stream)
+{
+    moe_status st = check_config(cfg);
+    if (st != MOE_OK) return st;
+    st = check_weights(experts);
+    if (st != MOE_OK) return st;
+    st = check_weights(united_out);
+    if (st != MOE_OK) return st;
+    if (n_calib < 0) return MOE_ERR_INVALID_ARG;
+    const bool want_loss = calib_x != nullptr && loss_per_group != nullptr && n_calib > 0;
+    if (calib_x && misaligned(calib_x)) return MOE_ERR_ALIGNMENT;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int m = cfg->n_experts, way = cfg->way, G = ceil_div(m, way);
+    const size_t n_elem = (size_t)cfg->d_model * cfg->d_ff;
+    Dims D;
+    Workspace W;
+    if (want_loss) {
+        st = check_T(cfg, n_calib);
+        if (st != MOE_OK) return st;
+        D = make_dims(*cfg, n_calib);
+        W = carve_workspace(D);
+        if (!workspace || workspace_bytes < W.total) return MOE_ERR_WORKSPACE;
+        if (reinterpret_cast<uintptr_t>(workspace) & 255u) return MOE_ERR_ALIGNMENT;
+    }
+    hipError_t e;
+    const void* src[3] = {experts->w1, experts->w3, experts->w2};
+    void* dst[3] = {const_cast<void*>(united_out->w1), const_cast<void*>(united_out->w3),
+                    const_cast<void*>(united_out->w2)};
+    for (int k = 0; k < 3; ++k) {
+        e = launch_united_mean(static_cast<const bf16_t*>(src[k]), m, way, n_elem, static_cast<bf16_t*>(dst[k]), s);
+        if (e != hipSuccess) return hip_fail(e, "moe_build_united/mean");
+    }
+    if (!want_loss) return MOE_OK;
+
+    const FfnWeights fe = to_ffn(experts), fu = to_ffn(united_out), fs{nullptr, nullptr, nullptr};
+    int32_t* unit_cnt = at<int32_t>(workspace, W.unit_cnt);
+    int32_t* unit_off = at<int32_t>(workspace, W.unit_off);
+    float* ones = at<float>(workspace, W.ones);
+    bf16_t* H = at<bf16_t>(workspace, W.H);
+    bf16_t* Yu = at<bf16_t>(workspace, W.Y);
+    bf16_t* Yo = Yu + (size_t)n_calib * D.d;
+    int32_t* tiles = at<int32_t>(workspace, W.tiles0);
+    const bf16_t* xb = static_cast<const bf16_t*>(calib_x);
+    e = launch_zero_f32(loss_per_group, G, s);
+    if (e != hipSuccess) return hip_fail(e, "moe_build_united/zero");
+    auto run_unit = [&](int u, bf16_t* Y) -> hipError_t {
+        hipError_t err = launch_single_unit(unit_cnt, unit_off, D.U, u, n_calib, ones, s);
+        if (err != hipSuccess) return err;
+        return launch_ffn(D, u, u + 1, D.F, n_calib, xb, nullptr, unit_cnt, unit_off, ones, fe, fu, fs, tiles, H, Y, s);
+    };
+    for (int g = 0; g < G; ++g) {
+        const int lo = g * way, hi = lo + way < m ? lo + way : m;
+        e = run_unit(m + g, Yu);
+        if (e != hipSuccess) return hip_fail(e, "moe_build_united/student");
+        for (int i = lo; i < hi; ++i) {
+            e = run_unit(i, Yo);
+            if (e != hipSuccess) return hip_fail(e, "moe_build_united/teacher");
+            e = launch_sqdiff_accumulate(Yu, Yo, (size_t)n_calib * D.d, 1.0f / ((float)(hi - lo) * (float)n_calib),
+                                         loss_per_group + g, s);
+            if (e != hipSuccess) return hip_fail(e, "moe_build_united/loss");
+        }
+    }
+    return MOE_OK;
+}
+
+moe_status moe_profile_enable(int32_t stage_mask)
+{
+    g_prof_mask = (unsigned)stage_mask & ((1u << MOE_N_STAGES) - 1u);
+    return MOE_OK;
+}
+
+moe_status moe_profile_collect(double* total_ms, int64_t* launches)
+{
+    if (!total_ms || !launches) return MOE_ERR_INVALID_ARG;
+    for (int i = 0; i < MOE_N_STAGES; ++i) { total_ms[i] = 0.0; launches[i] = 0; }
+    moe_status st = MOE_OK;
+    for (const ProfRecord& r : g_prof_records) {
+        float ms = 0.0f;
+        hipError_t e = hipEventSynchronize(r.b);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, r.a, r.b);
+        if (e != hipSuccess) st = hip_fail(e, "moe_profile_collect");
+        else { total_ms[r.stage] += (double)ms; launches[r.stage] += 1; }
+        g_prof_pool.push_back(r.a);
+        g_prof_pool.push_back(r.b);
+    }
+    g_prof_records.clear();
+    return st;
+}
+
+}  // extern "C"

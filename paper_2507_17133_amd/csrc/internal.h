@@ -1,0 +1,91 @@
+// Internal declarations shared by the translation units of libbrownout_moe.so.
+// Host-side launchers only; every kernel lives in the .hip file that launches it.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/brownout_moe.h"
+
+namespace bmoe {
+
+typedef __bf16 bf16_t;
+
+constexpr int kMaxExperts = 256;  // m
+constexpr int kMaxTopK = 32;      // K
+constexpr int kMaxShared = 8;     // N_s
+constexpr int kMaxUnits = kMaxExperts + kMaxExperts + kMaxShared;  // U
+constexpr int kSegTokens = 64;    // tokens per routing segment (one wavefront)
+constexpr int kMinTileRows = 32;  // smallest GEMM M tile
+
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Derived sizes of one (config, T) problem.
+struct Dims {
+    int T, d, F, m, K, way, G, Ns, Fs, U, slots, m_pad, Fmax;
+    int score_fn, add_residual;
+    int64_t row_cap;   // rows the row lists can hold: T*(K+Ns)
+    int n_seg;         // routing segments
+    int tile_cap;      // entries of one GEMM tile table
+};
+Dims make_dims(const moe_config& c, int T);
+
+// Carving of the caller's workspace.  All offsets are multiples of 256 bytes.
+struct Workspace {
+    size_t topk_idx, topk_w, expert_cnt, expert_unit, expert_in_s1, unit_cnt, unit_off, row_token, row_weight,
+        token_rows, n_rows, near_tie;                 // default homes of the moe_route_out fields
+    size_t gate_split;                                // [3][m_pad][d] bf16
+    size_t seg_cnt, seg_off;                          // [n_seg][U] int32
+    size_t tiles0, tiles1;                            // two GEMM tile tables: int32[4] header + int4 entries
+    size_t H;                                         // [h_rows][Fmax] bf16
+    size_t Y;                                         // [y_rows][d] bf16
+    size_t ones;                                      // [T] fp32 (build_united)
+    size_t total;
+    int64_t h_rows, y_rows;
+};
+Workspace carve_workspace(const Dims& D);
+
+// Resolved device pointers of the routing artefacts (caller's or workspace's).
+struct RouteBufs {
+    int32_t* topk_idx; float* topk_w; int32_t* expert_cnt; int32_t* expert_unit; uint8_t* expert_in_s1;
+    int32_t* unit_cnt; int32_t* unit_off; int32_t* row_token; float* row_weight; int32_t* token_rows;
+    int32_t* n_rows; uint8_t* near_tie;
+};
+
+// ---- profiling hooks (api.hip) ----
+void prof_begin(int stage, hipStream_t s);
+void prof_end(int stage, hipStream_t s);
+struct ProfScope {
+    int stage; hipStream_t s;
+    ProfScope(int st, hipStream_t str) : stage(st), s(str) { prof_begin(stage, s); }
+    ~ProfScope() { prof_end(stage, s); }
+};
+
+// ---- routing (route.hip) ----
+hipError_t launch_route(const Dims& D, const bf16_t* x, const float* gate_w, const float* gate_bias,
+                        double threshold, int full_brownout, const RouteBufs& R, bf16_t* gate_split,
+                        int32_t* seg_cnt, int32_t* seg_off, hipStream_t s);
+
+// ---- FFN (ffn.hip) ----
+struct FfnWeights { const bf16_t *w1, *w3, *w2; };
+// Runs W2(silu(W1 x)*(W3 x)) for the rows of units [u_lo,u_hi) listed in (unit_cnt, unit_off, gather),
+// writes Y[row][d] = row_weight[row] * FFN(x[gather ? gather[row] : row]).  Fdim is the FFN width of
+// these units.  Weight source of unit u: u<m experts[u]; u<m+G united[u-m]; else shared[u-m-G].
+hipError_t launch_ffn(const Dims& D, int u_lo, int u_hi, int Fdim, int64_t expected_rows, const bf16_t* x,
+                      const int32_t* gather, const int32_t* unit_cnt, const int32_t* unit_off,
+                      const float* row_weight, const FfnWeights& experts, const FfnWeights& united,
+                      const FfnWeights& shared, int32_t* tile_table, bf16_t* H, bf16_t* Y, hipStream_t s);
+hipError_t launch_combine(const Dims& D, const bf16_t* x, const bf16_t* Y, const int32_t* token_rows,
+                          bf16_t* out, hipStream_t s);
+
+// ---- united experts (united.hip) ----
+hipError_t launch_united_mean(const bf16_t* w, int m, int way, size_t n_elem, bf16_t* u, hipStream_t s);
+hipError_t launch_single_unit(int32_t* unit_cnt, int32_t* unit_off, int U, int u, int n, float* ones,
+                              hipStream_t s);
+hipError_t launch_zero_f32(float* p, int n, hipStream_t s);
+// loss[g] += scale * sum_{e<n} (a[e]-b[e])^2   (one block, deterministic)
+hipError_t launch_sqdiff_accumulate(const bf16_t* a, const bf16_t* b, size_t n, float scale, float* loss_g,
+                                    hipStream_t s);
+
+}  // namespace bmoe

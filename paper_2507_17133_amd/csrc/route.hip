@@ -1,0 +1,429 @@
+// Routing kernels of the BrownoutMoE layer for gfx950:
+//   prep     clear the expert counters, split the fp32 gate weights into three bf16 pieces
+//   gate     affinities s = x.e_i on MFMA (bf16 x 3-piece weights, fp64 running sums), TopK by
+//            wavefront shuffles, weights g, expert histogram        (Architecture of BrownoutMoE)
+//   count    Algorithm 1's S1/S2 split and unit map (every block, from the counts) and the rows
+//            each 64-token segment gives each unit                   (Brownout Approach, Algorithm 1)
+//   scan     offsets of segments inside units and of units
+//   scatter  row lists: row_token, row_weight, token_rows (stable: ascending token inside a unit)
+// No floating-point atomics anywhere; integer atomics only where the result does not depend on order.
+#include "internal.h"
+
+namespace bmoe {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ unsigned short f32_to_bf16_bits(float f)
+{
+    unsigned int u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);  // round to nearest, ties to even
+    return (unsigned short)(u >> 16);
+}
+__device__ __forceinline__ float bf16_bits_to_f32(unsigned short b) { return __uint_as_float(((unsigned int)b) << 16); }
+
+// ------------------------------------------------------------------------------------------------
+// prep: expert_cnt = 0; gate_w = hi + mid + lo with bf16 pieces (the three pieces carry 24 bits of
+// significand, so x(bf16) * piece products are exact in fp32 and their sum equals x*w to fp32 accuracy).
+// Rows m..m_pad-1 of every piece are zero.
+// ------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) prep_kernel(const float* __restrict__ gate_w, int m, int m_pad, int d,
+                                                   unsigned short* __restrict__ split, int32_t* __restrict__ expert_cnt)
+{
+    const size_t n = (size_t)m_pad * d;
+    const size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid < (size_t)m) expert_cnt[gid] = 0;
+    for (size_t i = gid; i < n; i += (size_t)gridDim.x * blockDim.x) {
+        const int e = (int)(i / d);
+        const float w = e < m ? gate_w[i] : 0.0f;
+        const unsigned short hi = f32_to_bf16_bits(w);
+        const float r1 = w - bf16_bits_to_f32(hi);
+        const unsigned short mid = f32_to_bf16_bits(r1);
+        const float r2 = r1 - bf16_bits_to_f32(mid);
+        const unsigned short lo = f32_to_bf16_bits(r2);
+        split[i] = hi;
+        split[n + i] = mid;
+        split[2 * n + i] = lo;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// gate: one block = 16 tokens x all experts.  Four wavefronts share the (expert tile, k slice) space:
+// NG = min(4, m_pad/16) expert groups of NTW 16-wide tiles, 4/NG k slices.  Each 64-wide k chunk is
+// accumulated from zero by six 16x16x32 bf16 MFMAs (lo, mid, hi pieces) and folded into an fp64 running
+// sum, which keeps the logit within a few 1e-8 of the exact dot product whatever d is.
+// ------------------------------------------------------------------------------------------------
+struct GateArgs {
+    const bf16_t* x; const unsigned short* split; const float* bias;
+    int T, d, m, m_pad, K, score_fn, NG, KS;
+    int32_t* topk_idx; float* topk_w; int32_t* expert_cnt; uint8_t* near_tie;
+};
+
+template <int NTW>
+__global__ void __launch_bounds__(256) gate_topk_kernel(GateArgs p)
+{
+    __shared__ double part[16 * kMaxExperts];   // [ks][token][m_pad], KS*m_pad <= 256
+    __shared__ float logit[16 * kMaxExperts];   // [token][m_pad]
+    __shared__ int hist[kMaxExperts];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int t0 = blockIdx.x * 16;
+    const int n_tiles = p.m_pad >> 4;
+    for (int i = tid; i < p.m_pad; i += 256) hist[i] = 0;
+
+    const bool active = wave < p.NG * p.KS;
+    const int ng = wave % p.NG, ks = wave / p.NG;
+    if (active) {
+        const int ksteps = p.d >> 5;
+        const int per = (ksteps + p.KS - 1) / p.KS;
+        const int k_lo = ks * per, k_hi = min(ksteps, k_lo + per);
+        const int trow = min(t0 + (lane & 15), p.T - 1);
+        const bf16_t* ap = p.x + (size_t)trow * p.d + 8 * (lane >> 4);
+        const size_t piece = (size_t)p.m_pad * p.d;
+        const unsigned short* bp[NTW];
+        bool tile_ok[NTW];
+#pragma unroll
+        for (int nt = 0; nt < NTW; ++nt) {
+            const int tile = ng * NTW + nt;
+            tile_ok[nt] = tile < n_tiles;
+            const int erow = (tile_ok[nt] ? tile : 0) * 16 + (lane & 15);
+            bp[nt] = p.split + (size_t)erow * p.d + 8 * (lane >> 4);
+        }
+        double sum[NTW][4];
+        f32x4 acc[NTW];
+#pragma unroll
+        for (int nt = 0; nt < NTW; ++nt) {
+            acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int v = 0; v < 4; ++v) sum[nt][v] = 0.0;
+        }
+        for (int kstep = k_lo; kstep < k_hi; ++kstep) {
+            const int ko = kstep << 5;
+            const bf16x8 a = *reinterpret_cast<const bf16x8*>(ap + ko);
+#pragma unroll
+            for (int nt = 0; nt < NTW; ++nt) {
+                if (!tile_ok[nt]) continue;
+                const bf16x8 b_lo = *reinterpret_cast<const bf16x8*>(bp[nt] + 2 * piece + ko);
+                const bf16x8 b_mid = *reinterpret_cast<const bf16x8*>(bp[nt] + piece + ko);
+                const bf16x8 b_hi = *reinterpret_cast<const bf16x8*>(bp[nt] + ko);
+                acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_lo, acc[nt], 0, 0, 0);
+                acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_mid, acc[nt], 0, 0, 0);
+                acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_hi, acc[nt], 0, 0, 0);
+            }
+            if (((kstep - k_lo) & 1) == 1 || kstep + 1 == k_hi) {
+#pragma unroll
+                for (int nt = 0; nt < NTW; ++nt) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) sum[nt][v] += (double)acc[nt][v];
+                    acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+            }
+        }
+        // MFMA 16x16 result layout: lane holds column (lane&15) = expert, rows 4*(lane>>4)+v = tokens.
+#pragma unroll
+        for (int nt = 0; nt < NTW; ++nt) {
+            if (!tile_ok[nt]) continue;
+            const int e = (ng * NTW + nt) * 16 + (lane & 15);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int tok = 4 * (lane >> 4) + v;
+                part[(ks * 16 + tok) * p.m_pad + e] = sum[nt][v];
+            }
+        }
+    }
+    __syncthreads();
+    for (int i = tid; i < 16 * p.m_pad; i += 256) {
+        const int tok = i / p.m_pad, e = i - tok * p.m_pad;
+        double s = 0.0;
+        for (int q = 0; q < p.KS; ++q) s += part[(q * 16 + tok) * p.m_pad + e];
+        if (p.bias != nullptr && e < p.m) s += (double)p.bias[e];
+        logit[i] = (float)s;
+    }
+    __syncthreads();
+
+    // TopK: each wavefront takes 4 tokens; lane holds experts lane, lane+64, ...
+    const int K = p.K;
+    const int n_pick = K < p.m ? K + 1 : K;    // one extra pick: the best loser, for the near-tie flag
+    for (int q = 0; q < 4; ++q) {
+        const int tok = wave * 4 + q;
+        const int t = t0 + tok;
+        if (t >= p.T) break;
+        float v[4];
+        unsigned taken = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int e = lane + 64 * c;
+            v[c] = e < p.m ? logit[tok * p.m_pad + e] : 0.0f;
+            if (e >= p.m) taken |= 1u << c;
+        }
+        float my_v = 0.0f;
+        int my_i = 0;
+        for (int j = 0; j < n_pick; ++j) {
+            float bv = 0.0f;
+            int bi = 0x7fffffff;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if (taken & (1u << c)) continue;
+                if (bi == 0x7fffffff || v[c] > bv) { bv = v[c]; bi = lane + 64 * c; }
+            }
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) {
+                const float ov = __shfl_xor(bv, off);
+                const int oi = __shfl_xor(bi, off);
+                const bool take = oi != 0x7fffffff && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi));
+                if (take) { bv = ov; bi = oi; }
+            }
+            bv = __shfl(bv, 0);
+            bi = __shfl(bi, 0);
+            if ((bi & 63) == lane) taken |= 1u << (bi >> 6);
+            if (lane == j) { my_v = bv; my_i = bi; }
+        }
+        // weights over lanes 0..K-1
+        const float top = __shfl(my_v, 0);
+        float num = 0.0f;
+        if (lane < K) num = p.score_fn == 0 ? expf(my_v - top) : 1.0f / (1.0f + expf(-my_v));
+        float den = num;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) den += __shfl_xor(den, off);
+        const float nxt = __shfl_down(my_v, 1);
+        const bool close = lane + 1 < n_pick && (my_v - nxt) < 1e-6f;
+        const unsigned long long any_close = __ballot(close);
+        if (lane < K) {
+            p.topk_idx[(size_t)t * K + lane] = my_i;
+            p.topk_w[(size_t)t * K + lane] = num / den;
+            atomicAdd(&hist[my_i], 1);
+        }
+        if (lane == 0 && p.near_tie != nullptr) p.near_tie[t] = any_close != 0ull ? 1 : 0;
+    }
+    __syncthreads();
+    for (int i = tid; i < p.m; i += 256)
+        if (hist[i] > 0) atomicAdd(&p.expert_cnt[i], hist[i]);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Algorithm 1 on the expert counts, one thread per expert (m <= 256).  Sorting is implicit: expert j
+// precedes expert i in the order "count descending, id ascending" iff cnt_j > cnt_i or (equal and
+// j < i); P_i = tokens covered before i is the sum of the counts of those j.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ void brownout_decide(const int* cnt_s, unsigned char* s2_s, int* unit_s, int m, int way,
+                                                double threshold, int full, int tid, bool write,
+                                                int32_t* expert_unit, uint8_t* expert_in_s1)
+{
+    bool in_s1 = false;
+    if (tid < m) {
+        const int c = cnt_s[tid];
+        long long P = 0, S = 0;
+        for (int j = 0; j < m; ++j) {
+            const int cj = cnt_s[j];
+            S += cj;
+            if (cj > c || (cj == c && j < tid)) P += cj;
+        }
+        in_s1 = (double)P < (double)S * threshold;
+        s2_s[tid] = (!in_s1 && c > 0) ? 1 : 0;
+    }
+    __syncthreads();
+    if (tid < m) {
+        const int g = tid / way, lo = g * way, hi = min(m, lo + way);
+        int members = 0;
+        for (int i = lo; i < hi; ++i) members += s2_s[i];
+        int unit = tid;
+        if (s2_s[tid]) {
+            if (full) unit = -1;
+            else if (members >= 2) unit = m + g;
+        }
+        unit_s[tid] = unit;
+        if (write) {
+            if (expert_unit) expert_unit[tid] = unit;
+            if (expert_in_s1) expert_in_s1[tid] = in_s1 ? 1 : 0;
+        }
+    }
+    __syncthreads();
+}
+
+struct RowArgs {
+    const int32_t* topk_idx; const float* topk_w; const int32_t* expert_cnt;
+    int32_t* expert_unit; uint8_t* expert_in_s1;
+    int T, K, m, way, G, Ns, U, n_seg, full;
+    double threshold;
+    int32_t* seg_cnt; int32_t* seg_off;
+    int32_t* unit_cnt; int32_t* unit_off; int32_t* n_rows;
+    int32_t* row_token; float* row_weight; int32_t* token_rows;
+};
+
+// One bit per token of the segment in bm[u]: token has a row in unit u.
+__device__ __forceinline__ void mark_units(const RowArgs& p, const int* unit_s, unsigned long long* bm, int t, int lane)
+{
+    if (t < p.T) {
+        const int32_t* idx = p.topk_idx + (size_t)t * p.K;
+        for (int j = 0; j < p.K; ++j) {
+            const int u = unit_s[idx[j]];
+            if (u < 0) continue;
+            atomicOr(&bm[u], 1ull << lane);   // a repeated united unit sets the same bit again
+        }
+        for (int s = 0; s < p.Ns; ++s) atomicOr(&bm[p.m + p.G + s], 1ull << lane);
+    }
+}
+
+__global__ void __launch_bounds__(256) route_count_kernel(RowArgs p)
+{
+    __shared__ int cnt_s[kMaxExperts];
+    __shared__ int unit_s[kMaxExperts];
+    __shared__ unsigned char s2_s[kMaxExperts];
+    __shared__ unsigned long long bm[4][kMaxUnits];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid < p.m) cnt_s[tid] = p.expert_cnt[tid];
+    for (int i = tid; i < 4 * kMaxUnits; i += 256) (&bm[0][0])[i] = 0ull;
+    __syncthreads();
+    brownout_decide(cnt_s, s2_s, unit_s, p.m, p.way, p.threshold, p.full, tid, blockIdx.x == 0, p.expert_unit,
+                    p.expert_in_s1);
+    const int seg = blockIdx.x * 4 + wave;
+    mark_units(p, unit_s, bm[wave], seg * kSegTokens + lane, lane);
+    __syncthreads();
+    if (seg < p.n_seg)
+        for (int u = lane; u < p.U; u += 64) p.seg_cnt[(size_t)seg * p.U + u] = __popcll(bm[wave][u]);
+}
+
+// One block: per unit, exclusive scan over segments; then exclusive scan over units.
+__global__ void __launch_bounds__(256) route_scan_kernel(RowArgs p)
+{
+    __shared__ int tot[kMaxUnits + 256];
+    __shared__ int wsum[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int u = tid; u < p.U; u += 256) {
+        int run = 0;
+        for (int sgm = 0; sgm < p.n_seg; ++sgm) {
+            const int c = p.seg_cnt[(size_t)sgm * p.U + u];
+            p.seg_off[(size_t)sgm * p.U + u] = run;
+            run += c;
+        }
+        tot[u] = run;
+        p.unit_cnt[u] = run;
+    }
+    __syncthreads();
+    // thread tid owns units [tid*per, tid*per+per)
+    const int per = (p.U + 255) / 256;
+    int local = 0;
+    for (int q = 0; q < per; ++q) {
+        const int u = tid * per + q;
+        if (u < p.U) local += tot[u];
+    }
+    int incl = local;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_up(incl, off);
+        if (lane >= off) incl += o;
+    }
+    if (lane == 63) wsum[wave] = incl;
+    __syncthreads();
+    int base = incl - local;
+    for (int w = 0; w < wave; ++w) base += wsum[w];
+    for (int q = 0; q < per; ++q) {
+        const int u = tid * per + q;
+        if (u < p.U) {
+            p.unit_off[u] = base;
+            base += tot[u];
+            if (u == p.U - 1) {
+                p.unit_off[p.U] = base;
+                if (p.n_rows) p.n_rows[0] = base;
+            }
+        }
+    }
+}
+
+__global__ void __launch_bounds__(256) route_scatter_kernel(RowArgs p)
+{
+    __shared__ int unit_s[kMaxExperts];
+    __shared__ unsigned long long bm[4][kMaxUnits];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid < p.m) unit_s[tid] = p.expert_unit[tid];
+    for (int i = tid; i < 4 * kMaxUnits; i += 256) (&bm[0][0])[i] = 0ull;
+    __syncthreads();
+    const int seg = blockIdx.x * 4 + wave;
+    const int t = seg * kSegTokens + lane;
+    mark_units(p, unit_s, bm[wave], t, lane);
+    __syncthreads();
+    if (t >= p.T) return;
+    const unsigned long long below = (1ull << lane) - 1ull;
+    const int32_t* idx = p.topk_idx + (size_t)t * p.K;
+    const float* wts = p.topk_w + (size_t)t * p.K;
+    const int slots = p.K + p.Ns;
+    const int32_t* soff = p.seg_off + (size_t)seg * p.U;
+    for (int j = 0; j < p.K; ++j) {
+        const int u = unit_s[idx[j]];
+        int row = -1;
+        if (u >= 0) {
+            bool first = true;
+            if (u >= p.m)
+                for (int q = 0; q < j; ++q)
+                    if (unit_s[idx[q]] == u) first = false;
+            if (first) {
+                row = p.unit_off[u] + soff[u] + __popcll(bm[wave][u] & below);
+                float w = wts[j];
+                if (u >= p.m)
+                    for (int q = j + 1; q < p.K; ++q)
+                        if (unit_s[idx[q]] == u) w += wts[q];     // merged entries, added in TopK order
+                p.row_token[row] = t;
+                p.row_weight[row] = w;
+            }
+        }
+        p.token_rows[(size_t)t * slots + j] = row;
+    }
+    for (int s = 0; s < p.Ns; ++s) {
+        const int u = p.m + p.G + s;
+        const int row = p.unit_off[u] + soff[u] + __popcll(bm[wave][u] & below);
+        p.row_token[row] = t;
+        p.row_weight[row] = 1.0f;
+        p.token_rows[(size_t)t * slots + p.K + s] = row;
+    }
+}
+
+hipError_t launch_route(const Dims& D, const bf16_t* x, const float* gate_w, const float* gate_bias,
+                        double threshold, int full_brownout, const RouteBufs& R, bf16_t* gate_split,
+                        int32_t* seg_cnt, int32_t* seg_off, hipStream_t s)
+{
+    {
+        ProfScope ps(MOE_STAGE_PREP, s);
+        const size_t n = (size_t)D.m_pad * D.d;
+        const int blocks = (int)std::min<size_t>((n + 255) / 256, 2048);
+        prep_kernel<<<blocks, 256, 0, s>>>(gate_w, D.m, D.m_pad, D.d, reinterpret_cast<unsigned short*>(gate_split),
+                                           R.expert_cnt);
+    }
+    {
+        ProfScope ps(MOE_STAGE_GATE, s);
+        GateArgs g;
+        g.x = x; g.split = reinterpret_cast<const unsigned short*>(gate_split); g.bias = gate_bias;
+        g.T = D.T; g.d = D.d; g.m = D.m; g.m_pad = D.m_pad; g.K = D.K; g.score_fn = D.score_fn;
+        const int n_tiles = D.m_pad / 16;
+        g.NG = n_tiles < 4 ? n_tiles : 4;
+        g.KS = 4 / g.NG;
+        const int ntw = ceil_div(n_tiles, g.NG);
+        g.topk_idx = R.topk_idx; g.topk_w = R.topk_w; g.expert_cnt = R.expert_cnt; g.near_tie = R.near_tie;
+        const int blocks = ceil_div(D.T, 16);
+        if (ntw == 1) gate_topk_kernel<1><<<blocks, 256, 0, s>>>(g);
+        else if (ntw == 2) gate_topk_kernel<2><<<blocks, 256, 0, s>>>(g);
+        else gate_topk_kernel<4><<<blocks, 256, 0, s>>>(g);
+    }
+    RowArgs p;
+    p.topk_idx = R.topk_idx; p.topk_w = R.topk_w; p.expert_cnt = R.expert_cnt;
+    p.expert_unit = R.expert_unit; p.expert_in_s1 = R.expert_in_s1;
+    p.T = D.T; p.K = D.K; p.m = D.m; p.way = D.way; p.G = D.G; p.Ns = D.Ns; p.U = D.U; p.n_seg = D.n_seg;
+    p.full = full_brownout; p.threshold = threshold;
+    p.seg_cnt = seg_cnt; p.seg_off = seg_off; p.unit_cnt = R.unit_cnt; p.unit_off = R.unit_off; p.n_rows = R.n_rows;
+    p.row_token = R.row_token; p.row_weight = R.row_weight; p.token_rows = R.token_rows;
+    const int seg_blocks = ceil_div(D.n_seg, 4);
+    {
+        ProfScope ps(MOE_STAGE_COUNT, s);
+        route_count_kernel<<<seg_blocks, 256, 0, s>>>(p);
+    }
+    {
+        ProfScope ps(MOE_STAGE_SCAN, s);
+        route_scan_kernel<<<1, 256, 0, s>>>(p);
+    }
+    {
+        ProfScope ps(MOE_STAGE_SCATTER, s);
+        route_scatter_kernel<<<seg_blocks, 256, 0, s>>>(p);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace bmoe

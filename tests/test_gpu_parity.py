@@ -1,0 +1,162 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element,
+on seeded inputs small enough for the oracle to finish in seconds but spanning several tiles,
+ragged tails and the degenerate cases of the method."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2507_17133_amd as P
+from oracle import oracle as O
+from paper_2507_17133_amd import workloads as WL
+from tests._util import OUT_TOL, check_route, npf, oracle_route, rel_err
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda"
+
+
+def _layer(cfg, seed=0):
+    torch.cuda.set_device(0)
+    L = WL.make_layer(cfg, seed, "cpu")
+    to = lambda t: None if t is None else t.to(DEV)
+    Lg = WL.Layer(cfg, to(L.x), to(L.gate_w), to(L.gate_b), tuple(to(a) for a in L.experts),
+                  None if L.shared is None else tuple(to(a) for a in L.shared), L.popularity)
+    return L, Lg
+
+
+SMALL = {
+    # name: (config, thresholds)
+    "tiny": (WL.CONFIGS["tiny"], [1.0, 0.75, 0.0]),
+    "tiny_way2": (WL.CONFIGS["tiny"].with_(way=2), [0.6, 0.3]),
+    "tiny_way3": (WL.CONFIGS["tiny"].with_(way=3), [0.5]),
+    "ragged_T": (WL.LayerConfig("ragged_T", T=333, d=128, F=192, m=12, K=3, way=4, zipf_s=1.0), [1.0, 0.5, 0.0]),
+    "one_token": (WL.LayerConfig("one_token", T=1, d=64, F=64, m=4, K=2, way=2), [1.0, 0.0]),
+    "one_expert": (WL.LayerConfig("one_expert", T=70, d=128, F=256, m=1, K=1, way=1), [1.0]),
+    "k_equals_m": (WL.LayerConfig("k_equals_m", T=50, d=64, F=128, m=4, K=4, way=2), [1.0, 0.4]),
+    "many_experts": (WL.LayerConfig("many_experts", T=700, d=256, F=128, m=128, K=8, way=8, zipf_s=1.0),
+                     [1.0, 0.5, 0.0]),
+    "max_experts_sigmoid_shared": (WL.LayerConfig("max_experts", T=300, d=192, F=128, m=256, K=8, way=8, n_shared=1,
+                                                  F_s=128, score_fn=1, zipf_s=1.1), [1.0, 0.6]),
+    "shared_other_width": (WL.LayerConfig("shared_other_width", T=130, d=128, F=256, m=6, K=2, way=4, n_shared=2,
+                                          F_s=64), [1.0, 0.5]),
+    "sixty_experts_way8": (WL.LayerConfig("sixty", T=260, d=128, F=64, m=60, K=4, way=8, zipf_s=1.0), [0.4]),
+    "way_above_m": (WL.LayerConfig("way_above_m", T=90, d=64, F=64, m=5, K=2, way=16), [0.5]),
+    "mid_tile": (WL.LayerConfig("mid_tile", T=600, d=128, F=256, m=8, K=2, way=4), [1.0, 0.5]),
+    "multi_tile": (WL.LayerConfig("multi_tile", T=1500, d=256, F=384, m=4, K=2, way=4, zipf_s=1.2), [1.0, 0.7]),
+}
+
+
+def _cases():
+    for name, (cfg, thrs) in SMALL.items():
+        for thr in thrs:
+            for full in ((False, True) if 0.0 < thr < 1.0 and name in ("tiny", "ragged_T", "many_experts") else (False,)):
+                yield pytest.param(cfg, thr, full, id=f"{name}-thr{thr}-{'full' if full else 'partial'}")
+
+
+@pytest.mark.parametrize("cfg,thr,full", list(_cases()))
+def test_route_and_forward(cfg, thr, full):
+    L, Lg = _layer(cfg)
+    c = P.config_of(cfg)
+    ref = oracle_route(L, cfg, thr, full)
+    R = P.moe_route(c, Lg.x, Lg.gate_w, Lg.gate_b, thr, full)
+    torch.cuda.synchronize()
+    idx, w, unit = check_route(R, ref, cfg, thr, full)
+
+    united_cpu = WL.make_random_united(cfg, 0, "cpu")
+    united = tuple(a.to(DEV) for a in united_cpu)
+    out = P.moe_forward(c, Lg.x, Lg.gate_w, Lg.gate_b, Lg.experts, united, Lg.shared, thr, full)
+    out_r = P.moe_forward(c, Lg.x, None, None, Lg.experts, united, Lg.shared, route=R)
+    torch.cuda.synchronize()
+    want = O.forward_tokens(npf(L.x), idx, w, unit, cfg.way, npf(L.experts), npf(united_cpu), npf(L.shared))
+    got = npf(out)
+    assert np.isfinite(got).all()
+    e = rel_err(got, want)
+    assert e <= OUT_TOL, f"max relative error {e}"
+    assert torch.equal(out, out_r), "forward with a precomputed route must equal routing internally"
+
+
+def test_residual():
+    cfg = WL.CONFIGS["tiny"]
+    L, Lg = _layer(cfg)
+    c = P.config_of(cfg)
+    c.add_residual = 1
+    ref = oracle_route(L, cfg, 1.0)
+    out = P.moe_forward(c, Lg.x, Lg.gate_w, Lg.gate_b, Lg.experts, None, None, 1.0)
+    want = O.forward_tokens(npf(L.x), ref.topk_idx, ref.topk_w, ref.expert_unit, cfg.way, npf(L.experts),
+                            add_residual=True)
+    assert rel_err(npf(out), want) <= OUT_TOL
+
+
+def test_full_brownout_threshold_zero_outputs_zero():
+    cfg = WL.CONFIGS["tiny"]
+    L, Lg = _layer(cfg)
+    out = P.moe_forward(P.config_of(cfg), Lg.x, Lg.gate_w, Lg.gate_b, Lg.experts, None, None, 0.0, True)
+    assert (npf(out) == 0).all()
+
+
+def test_threshold_sweep_is_monotone_in_united_rows():
+    cfg = SMALL["many_experts"][0]
+    L, Lg = _layer(cfg)
+    c = P.config_of(cfg)
+    prev = None
+    for thr in [0.0, 0.1, 0.2, 0.3, 0.4, 0.5, 0.6, 0.7, 0.8, 0.9, 1.0]:
+        R = P.moe_route(c, Lg.x, Lg.gate_w, Lg.gate_b, thr)
+        ref = oracle_route(L, cfg, thr)
+        check_route(R, ref, cfg, thr, False)
+        s1 = set(np.nonzero(npf(R.expert_in_s1))[0].tolist())
+        if prev is not None:
+            assert prev <= s1
+        prev = s1
+
+
+def test_build_united_mean_and_loss():
+    cfg = WL.LayerConfig("united", T=96, d=128, F=192, m=7, K=2, way=3)
+    L, Lg = _layer(cfg)
+    c = P.config_of(cfg)
+    calib_cpu = WL.make_activations(cfg, 0, "cpu", name="calib", n=96)
+    united, loss = P.moe_build_united(c, Lg.experts, calib_cpu.to(DEV))
+    torch.cuda.synchronize()
+    for k in range(3):
+        mean = O.united_mean(npf(L.experts[k]), cfg.way)                      # double
+        # round to bf16 (8 significant bits), nearest-even, straight from the double
+        mant, ex = np.frexp(mean)
+        want = np.ldexp(np.rint(mant * 256.0), ex - 8).astype(np.float32)
+        assert (npf(united[k]) == want).all()
+    ref_loss = O.united_loss(npf(calib_cpu), cfg.way, npf(L.experts), npf(united))
+    got = npf(loss)
+    assert np.allclose(got, ref_loss, rtol=3e-2, atol=1e-6), (got, ref_loss)
+    assert abs(got[2]) < 1e-6                                                   # single-member group
+    # way = 1: every united expert is its expert, loss 0
+    c1 = P.config_of(cfg.with_(way=1))
+    u1, l1 = P.moe_build_united(c1, Lg.experts, calib_cpu.to(DEV))
+    for k in range(3):
+        assert torch.equal(u1[k], Lg.experts[k])
+    assert (npf(l1) == 0).all()
+
+
+def test_identical_group_members_hide_brownout():
+    cfg = WL.LayerConfig("ident", T=200, d=128, F=128, m=6, K=2, way=3)
+    L, Lg = _layer(cfg)
+    c = P.config_of(cfg)
+    ex = tuple(a[::3].repeat_interleave(3, dim=0).contiguous() for a in Lg.experts)
+    un = tuple(a[::3].contiguous() for a in Lg.experts)
+    base = P.moe_forward(c, Lg.x, Lg.gate_w, Lg.gate_b, ex, un, None, 1.0)
+    for thr in (0.6, 0.0):
+        out = P.moe_forward(c, Lg.x, Lg.gate_w, Lg.gate_b, ex, un, None, thr)
+        assert rel_err(npf(out), npf(base)) <= 1e-2      # same FFNs, rows merged: only bf16 rounding differs
+
+
+def test_errors_are_reported_before_any_launch():
+    cfg = WL.CONFIGS["tiny"]
+    L, Lg = _layer(cfg)
+    c = P.config_of(cfg)
+    with pytest.raises(P.MoeError) as ei:
+        P.moe_route(c, Lg.x, Lg.gate_w, None, 1.5)
+    assert ei.value.status == -1
+    with pytest.raises(P.MoeError) as ei:
+        P.moe_forward(c, Lg.x, Lg.gate_w, None, Lg.experts, None, None, 0.5)      # united missing
+    assert ei.value.status == -1
+    small = torch.empty(1024, dtype=torch.uint8, device=DEV)
+    with pytest.raises(P.MoeError) as ei:
+        P.moe_route(c, Lg.x, Lg.gate_w, None, 1.0, workspace=small)
+    assert ei.value.status == -4
