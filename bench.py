@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""Benchmark of the BrownoutMoE layer forward on one MI355X.
+
+A step = one moe_forward call (gate, TopK, Algorithm 1, row scatter, both grouped GEMMs, combine)
+on a batch of synthetic tokens resident in HBM.  Default workload: the Mixtral-8x7B-shaped prefill
+layer (T=4096, d=4096, F=14336, 8 experts, top-2, Zipf(1.2) expert load, brownout fraction 0.3,
+one 8-way united expert).  Prints ONE JSON line on stdout; everything else goes to stderr.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="mixtral_prefill")
+    ap.add_argument("--fraction", type=float, default=None, help="brownout fraction f (threshold = 1-f)")
+    ap.add_argument("--way", type=int, default=None)
+    ap.add_argument("--tokens", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=None)
+    ap.add_argument("--stages", action="store_true", help="also print a per-kernel time breakdown to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        log("bench.py: this build measures one GPU only (no collectives, no sharding); run with --gpus 1")
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2507_17133_amd as P
+    from paper_2507_17133_amd import workloads as WL
+
+    torch.cuda.set_device(0)
+    dev = "cuda"
+    cfg = WL.CONFIGS[args.workload]
+    if args.way is not None:
+        cfg = cfg.with_(way=args.way)
+    if args.tokens is not None:
+        cfg = cfg.with_(T=args.tokens)
+    f = cfg.brownout_fractions[0] if args.fraction is None else args.fraction
+    threshold = 1.0 - f
+    c = P.config_of(cfg)
+
+    t0 = time.time()
+    L = WL.make_layer(cfg, 0, dev)
+    united, _ = P.moe_build_united(c, L.experts)
+    ws = P.alloc_workspace(c, cfg.T, dev)
+    out = torch.empty((cfg.T, cfg.d), dtype=torch.bfloat16, device=dev)
+    R = P.moe_route(c, L.x, L.gate_w, L.gate_b, threshold, workspace=ws)
+    torch.cuda.synchronize()
+    n_rows = int(R.n_rows.item())
+    unit_cnt = R.unit_cnt.cpu().numpy()
+    expert_cnt = R.expert_cnt.cpu().numpy()
+    n_shared_rows = cfg.T * cfg.n_shared
+    n_routed_rows = n_rows - n_shared_rows
+    active_units = int((unit_cnt > 0).sum())
+    united_rows_before_merge = int(expert_cnt[(R.expert_unit.cpu().numpy() >= cfg.m)].sum())
+    log(f"[setup {time.time()-t0:.1f}s] {cfg.name}: T={cfg.T} d={cfg.d} F={cfg.F} m={cfg.m} K={cfg.K} way={cfg.way} "
+        f"threshold={threshold:.2f} rows={n_rows} active_units={active_units}/{len(unit_cnt)}")
+    log(f"  expert load (tokens): max={expert_cnt.max()} mean={expert_cnt.mean():.1f} min={expert_cnt.min()} "
+        f"units with <16 rows: {int(((unit_cnt > 0) & (unit_cnt < 16)).sum())}; realised brownout fraction "
+        f"{united_rows_before_merge / float(cfg.T * cfg.K):.3f} (asked {f:.2f})")
+
+    def step():
+        P.moe_forward(c, L.x, L.gate_w, L.gate_b, L.experts, united, L.shared, threshold, False, None, out, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    P.profile_enable(["gemm1"])          # two HIP events per step around the dominant kernel, on its stream
+    t1 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    prof = P.profile_collect()
+    P.profile_disable()
+    ms_per_step = (t2 - t1) * 1e3 / args.steps
+    tokens_per_s = cfg.T * args.steps / (t2 - t1)
+
+    gemm1_ms = prof["gemm1"][0] / max(1, prof["gemm1"][1])
+    # algorithmic flops of GEMM1 per launch: rows x (W1 and W3) : 2*2*d*F per row (shared rows with their own F)
+    flops_gemm1 = 4.0 * cfg.d * (cfg.F * n_routed_rows + cfg.F_s * n_shared_rows)
+    flops_step = 6.0 * cfg.d * (cfg.F * n_routed_rows + cfg.F_s * n_shared_rows) + 2.0 * cfg.T * cfg.d * cfg.m
+    # algorithmic bytes per step: x in, out, gate, weights of the ACTIVE units only
+    unit_bytes = np.where(np.arange(len(unit_cnt)) < cfg.m + cfg.G, 3 * cfg.d * cfg.F * 2, 3 * cfg.d * cfg.F_s * 2)
+    bytes_step = 2 * cfg.T * cfg.d * 2 + cfg.d * cfg.m * 4 + int(unit_bytes[unit_cnt > 0].sum())
+    t_mfma = flops_step / (PEAK_BF16_TFLOPS * 1e12)
+    t_hbm = bytes_step / (PEAK_HBM_GBS * 1e9)
+    hbm_bound = t_hbm > t_mfma
+    if hbm_bound:
+        # weight streaming dominates: price GEMM1 by the bytes it must read (W1, W3 of active units + gathered x)
+        g1_bytes = int((unit_bytes[unit_cnt > 0] * 2 // 3).sum()) + n_rows * cfg.d * 2 + n_rows * cfg.F * 2
+        achieved = g1_bytes / (gemm1_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": achieved / PEAK_HBM_GBS, "traffic": None}
+    else:
+        achieved = flops_gemm1 / (gemm1_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None}
+    roofline["kernel"] = "ffn_gemm_kernel<SWIGLU> (GEMM1)"
+    roofline["kernel_ms"] = gemm1_ms
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{cfg.name}.json")
+    if os.path.exists(tpath):
+        try:
+            roofline["traffic"] = json.load(open(tpath)).get("gemm1_hbm_bytes_per_launch")
+        except Exception:
+            pass
+    log(f"  step {ms_per_step:.3f} ms  -> {tokens_per_s/1e6:.3f} M tok/s; layer roofline time "
+        f"{max(t_mfma, t_hbm)*1e3:.3f} ms ({'HBM' if hbm_bound else 'MFMA'}-bound) -> whole-step fraction "
+        f"{max(t_mfma, t_hbm)*1e3/ms_per_step:.3f}; GEMM1 {gemm1_ms:.3f} ms")
+
+    if args.stages:
+        P.profile_enable()
+        for _ in range(10):
+            step()
+        pr = P.profile_collect()
+        P.profile_disable()
+        log("  per-kernel ms (mean of 10): " + ", ".join(f"{k}={v[0]/max(1,v[1]):.4f}" for k, v in pr.items()))
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(cfg, L, united, threshold, args.cpu_sample_tokens)
+
+    line = {
+        "metric": "MoE-layer tokens/s at 1 MI355X", "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": cfg.name, "T": cfg.T, "d_model": cfg.d, "d_ff": cfg.F, "n_experts": cfg.m,
+                   "top_k": cfg.K, "way": cfg.way, "n_shared": cfg.n_shared, "brownout_fraction": f,
+                   "threshold": threshold, "rows": n_rows, "active_units": active_units,
+                   "layer_roofline_frac": max(t_mfma, t_hbm) * 1e3 / ms_per_step},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line), flush=True)
+
+
+def cpu_baseline(cfg, L, united, threshold, n_sample):
+    """The oracle as it stands, on the host cores: routing on every token, the layer equation on a
+    bounded sample of tokens (sized for roughly 10-30 s), throughput extrapolated linearly."""
+    import numpy as np
+    from oracle import oracle as O
+
+    f32 = lambda t: None if t is None else t.float().cpu().numpy()
+    x, gw, gb = f32(L.x), f32(L.gate_w), f32(L.gate_b)
+    t0 = time.perf_counter()
+    r = O.route(x, gw, gb, cfg.K, cfg.way, threshold, False, cfg.score_fn, cfg.n_shared)
+    t_route = time.perf_counter() - t0
+    per_token_flops = 6.0 * cfg.d * (cfg.F * cfg.K + cfg.F_s * cfg.n_shared)
+    if n_sample is None:
+        n_sample = int(max(8, min(cfg.T, 1e12 / per_token_flops)))        # ~1 TFLOP of plain loops
+    tokens = np.linspace(0, cfg.T - 1, n_sample).astype(np.int32)
+    cores = O.num_threads()
+    if cfg.m * cfg.d * cfg.F <= 6e8:
+        ex, un, sh = tuple(f32(a) for a in L.experts), tuple(f32(a) for a in united), \
+            None if L.shared is None else tuple(f32(a) for a in L.shared)
+        t0 = time.perf_counter()
+        O.forward_tokens(x, r.topk_idx, r.topk_w, r.expert_unit, cfg.way, ex, un, sh, tokens=tokens)
+        t_ffn = time.perf_counter() - t0
+    else:
+        src = {"expert": L.experts, "united": united, "shared": L.shared}
+        cache = {}
+
+        def get(kind, i):
+            if (kind, i) not in cache:
+                cache[(kind, i)] = tuple(f32(a[i]) for a in src[kind])
+            return cache[(kind, i)]
+        for t in tokens:                                           # fetch weights outside the timed part
+            for j in range(cfg.K):
+                u = int(r.expert_unit[r.topk_idx[t, j]])
+                if u >= 0:
+                    get("expert", u) if u < cfg.m else get("united", u - cfg.m)
+        for s in range(cfg.n_shared):
+            get("shared", s)
+        cores = 1                                                   # one row per FFN call: no parallel loop
+        t0 = time.perf_counter()
+        O.forward_tokens_lazy(x[tokens], r.topk_idx[tokens], r.topk_w[tokens], r.expert_unit, cfg.m, get,
+                              cfg.n_shared)
+        t_ffn = time.perf_counter() - t0
+    per_token = t_route / cfg.T + t_ffn / n_sample
+    log(f"  oracle: routing {t_route:.2f} s for {cfg.T} tokens, layer equation {t_ffn:.2f} s for {n_sample} tokens, "
+        f"{cores} threads")
+    return {"value": 1.0 / per_token, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"routing on all {cfg.T} tokens ({t_route:.2f} s) + layer equation on {n_sample} evenly spaced "
+                      f"tokens ({t_ffn:.2f} s), extrapolated linearly"}
+
+
+if __name__ == "__main__":
+    main()

@@ -88,18 +88,33 @@ struct GemmArgs {
     bf16_t* out; long ldo;
     const float* row_weight;
     int n_ntiles;
+    int group_m;                                // M tiles per L2 super-tile
 };
 
-template <int BM, int BN, int WM, int WN, bool SWIGLU>
+// Workgroup barrier that orders LDS traffic for the compiler without the vmcnt(0) wait __syncthreads()
+// implies: tiles still in flight to LDS (tracked by vmcnt) must stay in flight across it.  Every wave
+// waits for the loads it needs (s_waitcnt vmcnt) itself before arriving.
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+// s_waitcnt immediate that waits for vmcnt <= n only (gfx9 encoding: vmcnt in bits 3:0 and 15:14).
+__host__ __device__ constexpr int vmcnt_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | 0x0F70; }
+
+template <int BM, int BN, int WM, int WN, int BK, int NSTAGE, bool PINGPONG, bool SWIGLU>
 __global__ void __launch_bounds__(WM * WN * 64) ffn_gemm_kernel(GemmArgs p)
 {
-    constexpr int NTH = WM * WN * 64;
     constexpr int TM = BM / WM, TN = BN / WN;
     constexpr int FM = TM / 32, FN = TN / 32;
-    constexpr int ROWS_PER_PASS = NTH / 8;
-    constexpr int A_CH = BM / ROWS_PER_PASS, B_CH = BN / ROWS_PER_PASS;
-    constexpr int STAGE = (BM + BN) * 128;
-    static_assert(BM % ROWS_PER_PASS == 0 && BN % ROWS_PER_PASS == 0, "loader shape");
+    constexpr int RB = BK * 2;                    // bytes of one LDS row (one tile row, BK bf16)
+    constexpr int CPR = RB / 16;                  // 16-byte chunks per row
+    constexpr int WR = 256 / RB;                  // rows per 256-byte bank window (the LDS has 64 banks)
+    constexpr int RPG = 1024 / RB;                // rows one wave-wide 16-byte-per-lane load covers
+    constexpr int STAGE = (BM + BN) * RB;
+    static_assert(BK == 32 || BK == 64, "k tile");
     static_assert(!SWIGLU || (FN % 2 == 0), "gate/up tiles must pair inside a wavefront");
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
@@ -111,7 +126,13 @@ __global__ void __launch_bounds__(WM * WN * 64) ffn_gemm_kernel(GemmArgs p)
     if (bi >= chunk) return;
     const int L = (blockIdx.x & 7) * chunk + bi;
     if (L >= total) return;
-    const int nt = L / n_mt, mt = L - nt * n_mt;
+    // Super-tiles of group_m M tiles x all N tiles, M fastest: the ~32 blocks an XCD runs at a time
+    // cover group_m x (32/group_m) tiles and share their A and B panels in that XCD's L2.
+    const int gspan = p.group_m * p.n_ntiles;
+    const int gi = L / gspan, rem = L - gi * gspan;
+    const int mt_first = gi * p.group_m;
+    const int gsz = min(p.group_m, n_mt - mt_first);
+    const int nt = rem / gsz, mt = mt_first + (rem - nt * gsz);
     const int4 te = reinterpret_cast<const int4*>(p.table + 4)[mt];
     const int unit = te.x, row0 = te.y, nrows = te.z;
     const int src = unit < p.m ? 0 : (unit < p.m + p.G ? 1 : 2);
@@ -125,53 +146,47 @@ __global__ void __launch_bounds__(WM * WN * 64) ffn_gemm_kernel(GemmArgs p)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
 
-    // ---- loader: thread moves the 16-byte chunk (tid&7) of rows tid/8 + i*ROWS_PER_PASS ----
-    const int lc = tid & 7, lr = tid >> 3;
-    const bf16_t* aptr[A_CH];
-    const bf16_t* bptr[B_CH];
+    // ---- loader: direct global -> LDS (global_load_lds_dwordx4).  One wave instruction fills 1 KiB of
+    // LDS contiguously = RPG rows, lane l -> row l/CPR, slot l%CPR.  Slots are XOR-swizzled, on the global
+    // side: slot s of row r receives chunk s ^ ((r/WR) & (CPR-1)).  The LDS serves a ds_read_b128 sixteen
+    // lanes at a time across 64 banks (256 bytes = WR rows), so sixteen consecutive rows reading the
+    // same chunk must fall on sixteen different 16-byte bank groups; the r/WR term does that.
+    // Wave w moves row groups w, w+NW, ...
+    constexpr int NW = WM * WN;
+    constexpr int GROUPS = (BM + BN) / RPG;
+    constexpr int LD_PER_WAVE = GROUPS / NW;
+    static_assert(GROUPS % NW == 0, "loader shape");
+    const bf16_t* gptr[LD_PER_WAVE];
 #pragma unroll
-    for (int i = 0; i < A_CH; ++i) {
-        int r = lr + i * ROWS_PER_PASS;
-        r = r < nrows ? r : 0;                                     // ragged tile: re-read row 0, never stored
-        const long src_row = p.gather ? (long)p.gather[row0 + r] : (long)(row0 + r);
-        aptr[i] = p.A + src_row * p.lda + lc * 8;
-    }
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i) {
-        const int n = lr + i * ROWS_PER_PASS;
-        int col;
-        const bf16_t* W = Wa;
-        if (SWIGLU) {
-            const int w_n = n / TN, j = (n % TN) >> 5, c = n & 31;
-            col = n0 + (w_n * (TN / 64) + (j >> 1)) * 32 + c;
-            if (j & 1) W = Wb;
+    for (int i = 0; i < LD_PER_WAVE; ++i) {
+        const int row = (wave + i * NW) * RPG + lane / CPR;      // row of the stage: A rows, then B rows
+        const int l_chunk = (lane % CPR) ^ ((row / WR) & (CPR - 1));
+        if (row < BM) {
+            const int r = row < nrows ? row : 0;                   // ragged tile: re-read row 0, never stored
+            const long src_row = p.gather ? (long)p.gather[row0 + r] : (long)(row0 + r);
+            gptr[i] = p.A + src_row * p.lda + l_chunk * 8;
         } else {
-            col = n0 + n;
+            const int n = row - BM;
+            int col;
+            const bf16_t* W = Wa;
+            if (SWIGLU) {
+                const int w_n = n / TN, j = (n % TN) >> 5, c = n & 31;
+                col = n0 + (w_n * (TN / 64) + (j >> 1)) * 32 + c;
+                if (j & 1) W = Wb;
+            } else {
+                col = n0 + n;
+            }
+            col = col < p.N ? col : p.N - 1;                       // ragged N: clamp, never stored
+            gptr[i] = W + (size_t)col * p.K + l_chunk * 8;
         }
-        col = col < p.N ? col : p.N - 1;                           // ragged N: clamp, never stored
-        bptr[i] = W + (size_t)col * p.K + lc * 8;
     }
-    u32x4 ra[A_CH], rb[B_CH];
-    auto gload = [&](int kt) {
-        const int ko = kt * 64;
+    auto issue_loads = [&](int kt) {
+        char* dst = smem + (kt % NSTAGE) * STAGE + wave * 1024;
 #pragma unroll
-        for (int i = 0; i < A_CH; ++i) ra[i] = *reinterpret_cast<const u32x4*>(aptr[i] + ko);
-#pragma unroll
-        for (int i = 0; i < B_CH; ++i) rb[i] = *reinterpret_cast<const u32x4*>(bptr[i] + ko);
-    };
-    auto sstore = [&](int buf) {
-        char* As = smem + buf * STAGE;
-        char* Bs = As + BM * 128;
-#pragma unroll
-        for (int i = 0; i < A_CH; ++i) {
-            const int r = lr + i * ROWS_PER_PASS;
-            *reinterpret_cast<u32x4*>(As + r * 128 + ((lc ^ (r & 7)) << 4)) = ra[i];
-        }
-#pragma unroll
-        for (int i = 0; i < B_CH; ++i) {
-            const int r = lr + i * ROWS_PER_PASS;
-            *reinterpret_cast<u32x4*>(Bs + r * 128 + ((lc ^ (r & 7)) << 4)) = rb[i];
-        }
+        for (int i = 0; i < LD_PER_WAVE; ++i)
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void*)(gptr[i] + kt * BK),
+                (__attribute__((address_space(3))) void*)(dst + i * NW * 1024), 16, 0, 0);
     };
 
     f32x16 acc[FM][FN];
@@ -182,56 +197,137 @@ __global__ void __launch_bounds__(WM * WN * 64) ffn_gemm_kernel(GemmArgs p)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    const int nk = p.K >> 6;
-    gload(0);
-    sstore(0);
-    __syncthreads();
-    const int a_off = (wm * TM + (lane & 31)) * 128;
-    const int b_off = BM * 128 + (wn * TN + (lane & 31)) * 128;
-    for (int kt = 0; kt < nk; ++kt) {
-        if (kt + 1 < nk) gload(kt + 1);
-        const char* St = smem + (kt & 1) * STAGE;
+    // ---- main loop: NSTAGE LDS buffers, tiles kt+1 .. kt+NSTAGE-1 in flight while tile kt is multiplied.
+    const int nk = p.K / BK;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            const int sw = ((kk * 2 + (lane >> 5)) ^ (lane & 7)) << 4;
-            bf16x8 af[FM], bfr[FN];
+    for (int q = 0; q < NSTAGE - 1; ++q)
+        if (q < nk) issue_loads(q);
+    const int a_off = (wm * TM + (lane & 31)) * RB;
+    const int b_off = BM * RB + (wn * TN + (lane & 31)) * RB;
+    const int swz = ((lane & 31) / WR) & (CPR - 1);
+    constexpr int KK = BK / 16;
+    if constexpr (PINGPONG) {
+        // Two groups of waves (one wave of each per SIMD) run half a step out of phase: while one group
+        // issues its MFMAs for tile kt, the other reads its fragments of the next tile from LDS and
+        // queues global->LDS loads, so the matrix pipe of every SIMD always has a wave feeding it.
+        // Barriers separate the phases; group 1 starts one barrier late and group 0 ends one late.
+        static_assert(NSTAGE >= 2 && WM == 2 && BK % 32 == 0, "ping-pong shape");
+        constexpr int P = BK / 32;                            // steps (of 32 k) per tile
+        const int grp = wm;
+        if (NSTAGE - 2 < nk && NSTAGE > 2) __builtin_amdgcn_s_waitcnt(vmcnt_imm((NSTAGE - 2) * LD_PER_WAVE));
+        else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        lds_barrier();                                        // tile 0 is in LDS for everyone
+        if (grp == 1) lds_barrier();
+        for (int kt = 0; kt < nk; ++kt) {
+            const char* St = smem + (kt % NSTAGE) * STAGE;
 #pragma unroll
-            for (int i = 0; i < FM; ++i) af[i] = *reinterpret_cast<const bf16x8*>(St + a_off + i * 32 * 128 + sw);
+            for (int ph = 0; ph < P; ++ph) {
+                // -- memory phase.  At the first step of tile kt the buffer of tile kt-1 is free (both
+                // groups finished reading it two barriers ago): refill it with tile kt+NSTAGE-1.
+                if (ph == 0 && kt + NSTAGE - 1 < nk) issue_loads(kt + NSTAGE - 1);
+                bf16x8 af[2][FM], bfr[2][FN];
 #pragma unroll
-            for (int j = 0; j < FN; ++j) bfr[j] = *reinterpret_cast<const bf16x8*>(St + b_off + j * 32 * 128 + sw);
+                for (int kk = 0; kk < 2; ++kk) {
+                    const int sw = (((ph * 2 + kk) * 2 + (lane >> 5)) ^ swz) << 4;
 #pragma unroll
-            for (int i = 0; i < FM; ++i)
+                    for (int i = 0; i < FM; ++i)
+                        af[kk][i] = *reinterpret_cast<const bf16x8*>(St + a_off + i * 32 * RB + sw);
 #pragma unroll
-                for (int j = 0; j < FN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+                    for (int j = 0; j < FN; ++j)
+                        bfr[kk][j] = *reinterpret_cast<const bf16x8*>(St + b_off + j * 32 * RB + sw);
+                }
+                // fragments are in registers (lgkmcnt 0); at the last step of tile kt, tile kt+1 must
+                // have landed too: it is read right after the next barrier pair
+                if (ph == P - 1) {
+                    if (NSTAGE > 2 && kt + NSTAGE - 1 < nk)
+                        __builtin_amdgcn_s_waitcnt(vmcnt_imm((NSTAGE - 2) * LD_PER_WAVE) & 0xF0FF);
+                    else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0) & 0xF0FF);
+                } else {
+                    __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0) only
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                lds_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+                // -- compute phase
+                __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+                for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+                    for (int i = 0; i < FM; ++i)
+#pragma unroll
+                        for (int j = 0; j < FN; ++j)
+                            acc[i][j] =
+                                __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk][j], af[kk][i], acc[i][j], 0, 0, 0);
+                __builtin_amdgcn_s_setprio(0);
+                __builtin_amdgcn_sched_barrier(0);
+                lds_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
-        if (kt + 1 < nk) sstore((kt + 1) & 1);
-        __syncthreads();
+        if (grp == 0) lds_barrier();
+    } else {
+        for (int kt = 0; kt < nk; ++kt) {
+            // this wave's loads of tile kt have landed once at most the NSTAGE-2 younger tiles are outstanding
+            if (kt + NSTAGE - 2 < nk) __builtin_amdgcn_s_waitcnt(vmcnt_imm((NSTAGE - 2) * LD_PER_WAVE));
+            else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+            lds_barrier();        // every wave's part of tile kt is in LDS; nobody still reads tile kt-1's buffer
+            if (kt + NSTAGE - 1 < nk) issue_loads(kt + NSTAGE - 1);
+            const char* St = smem + (kt % NSTAGE) * STAGE;
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk) {
+                const int sw = ((kk * 2 + (lane >> 5)) ^ swz) << 4;
+                bf16x8 af[FM], bfr[FN];
+#pragma unroll
+                for (int i = 0; i < FM; ++i) af[i] = *reinterpret_cast<const bf16x8*>(St + a_off + i * 32 * RB + sw);
+#pragma unroll
+                for (int j = 0; j < FN; ++j) bfr[j] = *reinterpret_cast<const bf16x8*>(St + b_off + j * 32 * RB + sw);
+#pragma unroll
+                for (int i = 0; i < FM; ++i)
+#pragma unroll
+                    for (int j = 0; j < FN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+            }
+        }
     }
 
-    // ---- epilogue.  32x32 MFMA result: lane holds column lane&31, rows 8*(v/4) + 4*(lane>>5) + (v&3). ----
+    // ---- epilogue.  The MFMAs were issued as (weights x rows), so a lane holds, for output row lane&31,
+    // the four consecutive columns 8*(v>>2) + 4*(lane>>5) + 0..3 of each 32x32 tile: 8-byte bf16x4 stores.
     unsigned short* out = reinterpret_cast<unsigned short*>(p.out);
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
+        const int rl = wm * TM + i * 32 + (lane & 31);
+        if (rl >= nrows) continue;
+        unsigned short* orow = out + (long)(row0 + rl) * p.ldo;
+        if (SWIGLU) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int rl = wm * TM + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-            if (rl >= nrows) continue;
-            const long orow = (long)(row0 + rl) * p.ldo;
-            if (SWIGLU) {
+            for (int jp = 0; jp < FN / 2; ++jp) {
 #pragma unroll
-                for (int jp = 0; jp < FN / 2; ++jp) {
-                    const int col = n0 + (wn * (TN / 64) + jp) * 32 + (lane & 31);
-                    const float g = acc[i][2 * jp][v], u = acc[i][2 * jp + 1][v];
-                    const float h = g / (1.0f + __expf(-g)) * u;
-                    if (col < p.N) out[orow + col] = f2bf(h);
+                for (int q = 0; q < 4; ++q) {
+                    const int col = n0 + (wn * (TN / 64) + jp) * 32 + 8 * q + 4 * (lane >> 5);
+                    unsigned short h[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float g = acc[i][2 * jp][4 * q + e], u = acc[i][2 * jp + 1][4 * q + e];
+                        h[e] = f2bf(g * __frcp_rn(1.0f + __expf(-g)) * u);
+                    }
+                    if (col < p.N)
+                        *reinterpret_cast<uint2*>(orow + col) =
+                            make_uint2((unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16));
                 }
-            } else {
-                const float w = p.row_weight[row0 + rl];
+            }
+        } else {
+            const float w = p.row_weight[row0 + rl];
 #pragma unroll
-                for (int j = 0; j < FN; ++j) {
-                    const int col = n0 + wn * TN + j * 32 + (lane & 31);
-                    if (col < p.N) out[orow + col] = f2bf(acc[i][j][v] * w);
+            for (int j = 0; j < FN; ++j) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int col = n0 + wn * TN + j * 32 + 8 * q + 4 * (lane >> 5);
+                    unsigned short h[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) h[e] = f2bf(acc[i][j][4 * q + e] * w);
+                    if (col < p.N)
+                        *reinterpret_cast<uint2*>(orow + col) =
+                            make_uint2((unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16));
                 }
             }
         }
@@ -278,13 +374,14 @@ __global__ void __launch_bounds__(256) combine_kernel(const bf16_t* __restrict__
 }
 
 // ------------------------------------------------------------------------------------------------
-template <int BM, int BN, int WM, int WN, bool SWIGLU>
+template <int BM, int BN, int WM, int WN, int BK, int NSTAGE, bool PINGPONG, bool SWIGLU>
 static hipError_t launch_gemm(const GemmArgs& a, int max_mtiles, hipStream_t s)
 {
     constexpr int NTH = WM * WN * 64;
-    constexpr int LDS = 2 * (BM + BN) * 128;
+    constexpr int LDS = NSTAGE * (BM + BN) * BK * 2;
+    static_assert(LDS <= 160 * 1024, "LDS budget of one CU");
     static bool attr_set = false;
-    auto kern = ffn_gemm_kernel<BM, BN, WM, WN, SWIGLU>;
+    auto kern = ffn_gemm_kernel<BM, BN, WM, WN, BK, NSTAGE, PINGPONG, SWIGLU>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
@@ -314,10 +411,10 @@ template <bool SWIGLU>
 static hipError_t dispatch_gemm(int BM, const GemmArgs& a, int max_mtiles, hipStream_t s)
 {
     switch (BM) {
-        case 256: return launch_gemm<256, 256, 2, 4, SWIGLU>(a, max_mtiles, s);
-        case 128: return launch_gemm<128, 256, 2, 4, SWIGLU>(a, max_mtiles, s);
-        case 64: return launch_gemm<64, 256, 1, 4, SWIGLU>(a, max_mtiles, s);
-        default: return launch_gemm<32, 256, 1, 4, SWIGLU>(a, max_mtiles, s);
+        case 256: return launch_gemm<256, 256, 2, 4, 64, 2, true, SWIGLU>(a, max_mtiles, s);
+        case 128: return launch_gemm<128, 256, 2, 4, 64, 3, true, SWIGLU>(a, max_mtiles, s);
+        case 64: return launch_gemm<64, 256, 1, 4, 64, 3, false, SWIGLU>(a, max_mtiles, s);
+        default: return launch_gemm<32, 256, 1, 4, 64, 4, false, SWIGLU>(a, max_mtiles, s);
     }
 }
 
@@ -340,6 +437,9 @@ hipError_t launch_ffn(const Dims& D, int u_lo, int u_hi, int Fdim, int64_t expec
     g1.m = D.m; g1.G = D.G; g1.N = Fdim; g1.K = D.d;
     g1.out = H; g1.ldo = D.Fmax; g1.row_weight = nullptr;
     g1.n_ntiles = ceil_div(Fdim, 128);
+    int group_m = 4;
+    if (const char* e = std::getenv("BROWNOUT_MOE_GM")) group_m = std::max(1, std::atoi(e));
+    g1.group_m = group_m;
     {
         ProfScope ps(MOE_STAGE_GEMM1, s);
         hipError_t e = dispatch_gemm<true>(BM, g1, max_mtiles, s);
@@ -352,6 +452,7 @@ hipError_t launch_ffn(const Dims& D, int u_lo, int u_hi, int Fdim, int64_t expec
     g2.m = D.m; g2.G = D.G; g2.N = D.d; g2.K = Fdim;
     g2.out = Y; g2.ldo = D.d; g2.row_weight = row_weight;
     g2.n_ntiles = ceil_div(D.d, 256);
+    g2.group_m = group_m;
     {
         ProfScope ps(MOE_STAGE_GEMM2, s);
         hipError_t e = dispatch_gemm<false>(BM, g2, max_mtiles, s);
