@@ -36,6 +36,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=None)
     ap.add_argument("--stages", action="store_true", help="also print a per-kernel time breakdown to stderr")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="only run a plain 1 GiB device-to-device copy three times (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build measures one GPU only (no collectives, no sharding); run with --gpus 1")
@@ -49,6 +51,14 @@ def main():
 
     torch.cuda.set_device(0)
     dev = "cuda"
+    if args.copy_probe:
+        src = torch.ones(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        log("copy probe: 3 device copies of 1 GiB (each reads 1 GiB and writes 1 GiB)")
+        return
     cfg = WL.CONFIGS[args.workload]
     if args.way is not None:
         cfg = cfg.with_(way=args.way)
@@ -117,12 +127,13 @@ def main():
                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None}
     roofline["kernel"] = "ffn_gemm_kernel<SWIGLU> (GEMM1)"
     roofline["kernel_ms"] = gemm1_ms
-    tpath = os.path.join(ROOT, "profiles", f"traffic_{cfg.name}.json")
-    if os.path.exists(tpath):
-        try:
-            roofline["traffic"] = json.load(open(tpath)).get("gemm1_hbm_bytes_per_launch")
-        except Exception:
-            pass
+    # HBM bytes of one GEMM1 launch as counted by rocprofv3 (FETCH_SIZE + WRITE_SIZE, scaled by a copy
+    # probe): taken from the committed profile summary of this workload, if there is one
+    tpath = os.path.join(ROOT, "profiles", f"moe_forward_{cfg.name}.txt")
+    if os.path.exists(tpath) and args.fraction is None and args.way is None and args.tokens is None:
+        for ln in open(tpath):
+            if ln.startswith("gemm1_hbm_bytes_per_launch"):
+                roofline["traffic"] = float(ln.split("=")[1])
     log(f"  step {ms_per_step:.3f} ms  -> {tokens_per_s/1e6:.3f} M tok/s; layer roofline time "
         f"{max(t_mfma, t_hbm)*1e3:.3f} ms ({'HBM' if hbm_bound else 'MFMA'}-bound) -> whole-step fraction "
         f"{max(t_mfma, t_hbm)*1e3/ms_per_step:.3f}; GEMM1 {gemm1_ms:.3f} ms")

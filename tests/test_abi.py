@@ -1,0 +1,116 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every function the
+header declares, and rejects bad arguments before touching the device."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2507_17133_amd as P
+from paper_2507_17133_amd import binding as B
+
+HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "brownout_moe.h")
+
+if not os.path.exists(B.LIB_PATH):
+    from paper_2507_17133_amd import build as _build
+    _build.build()
+
+
+def _declared():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(moe_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_function_is_exported():
+    names = _declared()
+    assert {"moe_build_united", "moe_route", "moe_forward", "moe_workspace_size"} <= set(names)
+    lib = C.CDLL(B.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in brownout_moe.h but not exported"
+    assert set(B.EXPORTS) == set(names)
+
+
+def test_status_strings():
+    L = P.lib()
+    for code in range(0, -7, -1):
+        assert L.moe_status_string(code)
+    assert L.moe_status_string(0) == b"ok"
+
+
+def test_workspace_size_grows_with_tokens_and_rejects_bad_shapes():
+    good = P.make_config(4096, 14336, 8, 2, 8)
+    a, b = P.workspace_size(good, 256), P.workspace_size(good, 4096)
+    assert 0 < a < b and a % 256 == 0
+    for bad, status in [
+        (P.make_config(4096, 14336, 8, 9, 8), -1),        # top_k > n_experts
+        (P.make_config(4096, 14336, 8, 2, 0), -1),        # way < 1
+        (P.make_config(4096, 14336, 0, 1, 1), -1),        # no experts
+        (P.make_config(4100, 14336, 8, 2, 8), -2),        # d not a multiple of 64
+        (P.make_config(4096, 100, 8, 2, 8), -2),          # F not a multiple of 64
+        (P.make_config(4096, 14336, 300, 2, 8), -2),      # too many experts
+        (P.make_config(4096, 14336, 8, 2, 8, 1, 0), -2),  # shared expert without a width
+        (P.make_config(4096, 14336, 8, 2, 8, score_fn=7), -1),
+    ]:
+        with pytest.raises(P.MoeError) as ei:
+            P.workspace_size(bad, 128)
+        assert ei.value.status == status, bad
+    with pytest.raises(P.MoeError) as ei:
+        P.workspace_size(good, 0)
+    assert ei.value.status == -1
+
+
+def _fake(addr=0x10000):
+    return C.c_void_p(addr)
+
+
+def test_route_and_forward_validate_before_launching():
+    """Dummy non-null pointers: every one of these calls must fail in host-side validation,
+    i.e. return an error without dereferencing anything."""
+    L = P.lib()
+    cfg = P.make_config(256, 512, 8, 2, 8)
+    ro = B.moe_route_out()
+    ws_bytes = P.workspace_size(cfg, 64)
+
+    def route(x=_fake(), T=64, gw=_fake(0x20000), thr=1.0, out=C.byref(ro), ws=_fake(0x100000), nbytes=None):
+        return L.moe_route(C.byref(cfg), x, T, gw, None, thr, 0, out, ws, ws_bytes if nbytes is None else nbytes, None)
+
+    assert route(thr=1.5) == -1
+    assert route(thr=-0.1) == -1
+    assert route(thr=float("nan")) == -1
+    assert route(T=0) == -1
+    assert route(x=None) == -1
+    assert route(gw=None) == -1
+    assert route(out=None) == -1
+    assert route(x=_fake(0x10004)) == -3
+    assert route(ws=None) == -4
+    assert route(nbytes=ws_bytes - 1) == -4
+
+    w = B.moe_ffn_weights(0x30000, 0x40000, 0x50000)
+
+    def fwd(thr=1.0, united=None, shared=None, experts=C.byref(w), out=_fake(0x60000), full=0, nbytes=ws_bytes):
+        return L.moe_forward(C.byref(cfg), _fake(), 64, _fake(0x20000), None, experts, united, shared, thr, full,
+                             None, out, _fake(0x100000), nbytes, None)
+
+    assert fwd(thr=0.5) == -1                 # partial brownout needs united experts
+    assert fwd(experts=None) == -1
+    assert fwd(out=None) == -1
+    assert fwd(shared=C.byref(w)) == -1       # shared weights given but n_shared == 0
+    assert fwd(thr=2.0) == -1
+    assert fwd(nbytes=16) == -4
+    half = B.moe_ffn_weights(0x30000, None, 0x50000)
+    assert fwd(experts=C.byref(half)) == -1
+    cfg_s = P.make_config(256, 512, 8, 2, 8, 1, 512)
+    assert L.moe_forward(C.byref(cfg_s), _fake(), 64, _fake(0x20000), None, C.byref(w), None, None, 1.0, 0, None,
+                         _fake(0x60000), _fake(0x100000), 1 << 40, None) == -1      # shared expert weights missing
+
+
+def test_build_united_validates():
+    L = P.lib()
+    cfg = P.make_config(256, 512, 8, 2, 4)
+    w = B.moe_ffn_weights(0x30000, 0x40000, 0x50000)
+    assert L.moe_build_united(C.byref(cfg), None, C.byref(w), None, 0, None, None, 0, None) == -1
+    assert L.moe_build_united(C.byref(cfg), C.byref(w), None, None, 0, None, None, 0, None) == -1
+    assert L.moe_build_united(C.byref(cfg), C.byref(w), C.byref(w), None, -1, None, None, 0, None) == -1
+    # calibration requested but no workspace
+    assert L.moe_build_united(C.byref(cfg), C.byref(w), C.byref(w), _fake(), 16, _fake(0x70000), None, 0, None) == -4
