@@ -2,6 +2,7 @@
 #include "internal.h"
 
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -31,7 +32,26 @@ Dims make_dims(const moe_config& c, int T)
     D.row_cap = (int64_t)T * D.slots;
     D.n_seg = ceil_div(T, kSegTokens);
     D.tile_cap = (int)(D.row_cap / kMinTileRows) + D.U;
+    // GEMM2 has few, long tiles (N = d): split K until about six rounds of blocks fill the 256 CUs.
+    const int bm = pick_tile_rows((int64_t)T * D.K / D.m);
+    const int64_t tiles2 = (D.row_cap / bm + (D.m + D.G) / 2 + D.Ns) * (int64_t)ceil_div(D.d, 256);
+    int ks = 1;
+    while (ks < 8 && tiles2 * ks < 1536 && (D.F / 64) / (ks * 2) >= 8) ks *= 2;
+    D.ksplit = ks;
+    D.y_plane = D.row_cap * (int64_t)D.d;
     return D;
+}
+
+int pick_tile_rows(int64_t expected_rows_per_unit)
+{
+    if (const char* e = std::getenv("BROWNOUT_MOE_BM")) {
+        const int v = std::atoi(e);
+        if (v == 32 || v == 64 || v == 128 || v == 256) return v;
+    }
+    if (expected_rows_per_unit >= 384) return 256;
+    if (expected_rows_per_unit >= 96) return 128;
+    if (expected_rows_per_unit >= 40) return 64;
+    return 32;
 }
 
 Workspace carve_workspace(const Dims& D)
@@ -57,7 +77,7 @@ Workspace carve_workspace(const Dims& D)
     W.tiles0 = take(16 + (size_t)D.tile_cap * 16);
     W.tiles1 = take(16 + (size_t)D.tile_cap * 16);
     W.h_rows = D.row_cap;
-    W.y_rows = D.row_cap > 2 * (int64_t)D.T ? D.row_cap : 2 * (int64_t)D.T;
+    W.y_rows = D.row_cap * D.ksplit > 2 * (int64_t)D.T ? D.row_cap * D.ksplit : 2 * (int64_t)D.T;
     W.H = take((size_t)W.h_rows * D.Fmax * 2);
     W.Y = take((size_t)W.y_rows * D.d * 2);
     W.ones = take((size_t)D.T * 4);
@@ -330,6 +350,7 @@ moe_status moe_build_united(const moe_config* cfg, const moe_ffn_weights* expert
         st = check_T(cfg, n_calib);
         if (st != MOE_OK) return st;
         D = make_dims(*cfg, n_calib);
+        D.ksplit = 1;          // the loss kernel reads single-plane FFN outputs
         W = carve_workspace(D);
         if (!workspace || workspace_bytes < W.total) return MOE_ERR_WORKSPACE;
         if (reinterpret_cast<uintptr_t>(workspace) & 255u) return MOE_ERR_ALIGNMENT;

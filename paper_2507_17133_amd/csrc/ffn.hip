@@ -89,6 +89,7 @@ struct GemmArgs {
     const float* row_weight;
     int n_ntiles;
     int group_m;                                // M tiles per L2 super-tile
+    int ksplit; long plane;                     // GEMM2 only: K split into ksplit slices, slice s writes out + s*plane
 };
 
 // Workgroup barrier that orders LDS traffic for the compiler without the vmcnt(0) wait __syncthreads()
@@ -101,209 +102,92 @@ __device__ __forceinline__ void lds_barrier()
     asm volatile("" ::: "memory");
 }
 
-// s_waitcnt immediate that waits for vmcnt <= n only (gfx9 encoding: vmcnt in bits 3:0 and 15:14).
-__host__ __device__ constexpr int vmcnt_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | 0x0F70; }
+// s_waitcnt immediates (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8).
+__host__ __device__ constexpr int vmcnt_imm(int n) { return (n & 0xF) | ((n >> 4) << 14) | 0x0F70; }       // vmcnt <= n
+__host__ __device__ constexpr int vmcnt_lgkm0_imm(int n) { return vmcnt_imm(n) & 0xF0FF; }                 // and lgkmcnt 0
 
-template <int BM, int BN, int WM, int WN, int BK, int NSTAGE, bool PINGPONG, bool SWIGLU>
-__global__ void __launch_bounds__(WM * WN * 64) ffn_gemm_kernel(GemmArgs p)
+// Which tile a block works on.
+struct Tile {
+    int unit, row0, nrows, nt, n0, kslice;
+    const bf16_t *Wa, *Wb;
+};
+
+template <int BNC, bool SWIGLU>
+__device__ __forceinline__ bool decode_tile(const GemmArgs& p, Tile& t)
 {
-    constexpr int TM = BM / WM, TN = BN / WN;
-    constexpr int FM = TM / 32, FN = TN / 32;
-    constexpr int RB = BK * 2;                    // bytes of one LDS row (one tile row, BK bf16)
-    constexpr int CPR = RB / 16;                  // 16-byte chunks per row
-    constexpr int WR = 256 / RB;                  // rows per 256-byte bank window (the LDS has 64 banks)
-    constexpr int RPG = 1024 / RB;                // rows one wave-wide 16-byte-per-lane load covers
-    constexpr int STAGE = (BM + BN) * RB;
-    static_assert(BK == 32 || BK == 64, "k tile");
-    static_assert(!SWIGLU || (FN % 2 == 0), "gate/up tiles must pair inside a wavefront");
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-
-    // ---- which tile ----
     const int n_mt = p.table[0];
-    const int total = n_mt * p.n_ntiles;
+    const int tiles = n_mt * p.n_ntiles;
+    const int total = tiles * p.ksplit;
     const int chunk = (total + 7) >> 3;
     const int bi = blockIdx.x >> 3;
-    if (bi >= chunk) return;
-    const int L = (blockIdx.x & 7) * chunk + bi;
-    if (L >= total) return;
+    if (bi >= chunk) return false;
+    const int Lfull = (blockIdx.x & 7) * chunk + bi;           // block id mod 8 = XCD: contiguous range per XCD
+    if (Lfull >= total) return false;
+    t.kslice = Lfull / tiles;
+    const int L = Lfull - t.kslice * tiles;
     // Super-tiles of group_m M tiles x all N tiles, M fastest: the ~32 blocks an XCD runs at a time
     // cover group_m x (32/group_m) tiles and share their A and B panels in that XCD's L2.
     const int gspan = p.group_m * p.n_ntiles;
     const int gi = L / gspan, rem = L - gi * gspan;
     const int mt_first = gi * p.group_m;
     const int gsz = min(p.group_m, n_mt - mt_first);
-    const int nt = rem / gsz, mt = mt_first + (rem - nt * gsz);
+    t.nt = rem / gsz;
+    const int mt = mt_first + (rem - t.nt * gsz);
     const int4 te = reinterpret_cast<const int4*>(p.table + 4)[mt];
-    const int unit = te.x, row0 = te.y, nrows = te.z;
-    const int src = unit < p.m ? 0 : (unit < p.m + p.G ? 1 : 2);
-    const int widx = unit - (src == 0 ? 0 : (src == 1 ? p.m : p.m + p.G));
+    t.unit = te.x; t.row0 = te.y; t.nrows = te.z;
+    const int src = t.unit < p.m ? 0 : (t.unit < p.m + p.G ? 1 : 2);
+    const int widx = t.unit - (src == 0 ? 0 : (src == 1 ? p.m : p.m + p.G));
     const size_t wsz = (size_t)p.N * p.K;
-    const bf16_t* Wa = (src == 0 ? p.wa0 : (src == 1 ? p.wa1 : p.wa2)) + (size_t)widx * wsz;
-    const bf16_t* Wb = SWIGLU ? (src == 0 ? p.wb0 : (src == 1 ? p.wb1 : p.wb2)) + (size_t)widx * wsz : nullptr;
-    constexpr int BNC = SWIGLU ? BN / 2 : BN;    // output columns per block
-    const int n0 = nt * BNC;
+    t.Wa = (src == 0 ? p.wa0 : (src == 1 ? p.wa1 : p.wa2)) + (size_t)widx * wsz;
+    t.Wb = SWIGLU ? (src == 0 ? p.wb0 : (src == 1 ? p.wb1 : p.wb2)) + (size_t)widx * wsz : nullptr;
+    t.n0 = t.nt * BNC;
+    return true;
+}
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WN, wn = wave % WN;
+// Global row of A for tile row `row` (ragged tiles re-read row 0; such rows are never stored).
+__device__ __forceinline__ const bf16_t* a_row_ptr(const GemmArgs& p, const Tile& t, int row)
+{
+    const int r = row < t.nrows ? row : 0;
+    const long src_row = p.gather ? (long)p.gather[t.row0 + r] : (long)(t.row0 + r);
+    return p.A + src_row * p.lda;
+}
 
-    // ---- loader: direct global -> LDS (global_load_lds_dwordx4).  One wave instruction fills 1 KiB of
-    // LDS contiguously = RPG rows, lane l -> row l/CPR, slot l%CPR.  Slots are XOR-swizzled, on the global
-    // side: slot s of row r receives chunk s ^ ((r/WR) & (CPR-1)).  The LDS serves a ds_read_b128 sixteen
-    // lanes at a time across 64 banks (256 bytes = WR rows), so sixteen consecutive rows reading the
-    // same chunk must fall on sixteen different 16-byte bank groups; the r/WR term does that.
-    // Wave w moves row groups w, w+NW, ...
-    constexpr int NW = WM * WN;
-    constexpr int GROUPS = (BM + BN) / RPG;
-    constexpr int LD_PER_WAVE = GROUPS / NW;
-    static_assert(GROUPS % NW == 0, "loader shape");
-    const bf16_t* gptr[LD_PER_WAVE];
-#pragma unroll
-    for (int i = 0; i < LD_PER_WAVE; ++i) {
-        const int row = (wave + i * NW) * RPG + lane / CPR;      // row of the stage: A rows, then B rows
-        const int l_chunk = (lane % CPR) ^ ((row / WR) & (CPR - 1));
-        if (row < BM) {
-            const int r = row < nrows ? row : 0;                   // ragged tile: re-read row 0, never stored
-            const long src_row = p.gather ? (long)p.gather[row0 + r] : (long)(row0 + r);
-            gptr[i] = p.A + src_row * p.lda + l_chunk * 8;
-        } else {
-            const int n = row - BM;
-            int col;
-            const bf16_t* W = Wa;
-            if (SWIGLU) {
-                const int w_n = n / TN, j = (n % TN) >> 5, c = n & 31;
-                col = n0 + (w_n * (TN / 64) + (j >> 1)) * 32 + c;
-                if (j & 1) W = Wb;
-            } else {
-                col = n0 + n;
-            }
-            col = col < p.N ? col : p.N - 1;                       // ragged N: clamp, never stored
-            gptr[i] = W + (size_t)col * p.K + l_chunk * 8;
-        }
-    }
-    auto issue_loads = [&](int kt) {
-        char* dst = smem + (kt % NSTAGE) * STAGE + wave * 1024;
-#pragma unroll
-        for (int i = 0; i < LD_PER_WAVE; ++i)
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void*)(gptr[i] + kt * BK),
-                (__attribute__((address_space(3))) void*)(dst + i * NW * 1024), 16, 0, 0);
-    };
-
-    f32x16 acc[FM][FN];
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-
-    // ---- main loop: NSTAGE LDS buffers, tiles kt+1 .. kt+NSTAGE-1 in flight while tile kt is multiplied.
-    const int nk = p.K / BK;
-#pragma unroll
-    for (int q = 0; q < NSTAGE - 1; ++q)
-        if (q < nk) issue_loads(q);
-    const int a_off = (wm * TM + (lane & 31)) * RB;
-    const int b_off = BM * RB + (wn * TN + (lane & 31)) * RB;
-    const int swz = ((lane & 31) / WR) & (CPR - 1);
-    constexpr int KK = BK / 16;
-    if constexpr (PINGPONG) {
-        // Two groups of waves (one wave of each per SIMD) run half a step out of phase: while one group
-        // issues its MFMAs for tile kt, the other reads its fragments of the next tile from LDS and
-        // queues global->LDS loads, so the matrix pipe of every SIMD always has a wave feeding it.
-        // Barriers separate the phases; group 1 starts one barrier late and group 0 ends one late.
-        static_assert(NSTAGE >= 2 && WM == 2 && BK % 32 == 0, "ping-pong shape");
-        constexpr int P = BK / 32;                            // steps (of 32 k) per tile
-        const int grp = wm;
-        if (NSTAGE - 2 < nk && NSTAGE > 2) __builtin_amdgcn_s_waitcnt(vmcnt_imm((NSTAGE - 2) * LD_PER_WAVE));
-        else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-        lds_barrier();                                        // tile 0 is in LDS for everyone
-        if (grp == 1) lds_barrier();
-        for (int kt = 0; kt < nk; ++kt) {
-            const char* St = smem + (kt % NSTAGE) * STAGE;
-#pragma unroll
-            for (int ph = 0; ph < P; ++ph) {
-                // -- memory phase.  At the first step of tile kt the buffer of tile kt-1 is free (both
-                // groups finished reading it two barriers ago): refill it with tile kt+NSTAGE-1.
-                if (ph == 0 && kt + NSTAGE - 1 < nk) issue_loads(kt + NSTAGE - 1);
-                bf16x8 af[2][FM], bfr[2][FN];
-#pragma unroll
-                for (int kk = 0; kk < 2; ++kk) {
-                    const int sw = (((ph * 2 + kk) * 2 + (lane >> 5)) ^ swz) << 4;
-#pragma unroll
-                    for (int i = 0; i < FM; ++i)
-                        af[kk][i] = *reinterpret_cast<const bf16x8*>(St + a_off + i * 32 * RB + sw);
-#pragma unroll
-                    for (int j = 0; j < FN; ++j)
-                        bfr[kk][j] = *reinterpret_cast<const bf16x8*>(St + b_off + j * 32 * RB + sw);
-                }
-                // fragments are in registers (lgkmcnt 0); at the last step of tile kt, tile kt+1 must
-                // have landed too: it is read right after the next barrier pair
-                if (ph == P - 1) {
-                    if (NSTAGE > 2 && kt + NSTAGE - 1 < nk)
-                        __builtin_amdgcn_s_waitcnt(vmcnt_imm((NSTAGE - 2) * LD_PER_WAVE) & 0xF0FF);
-                    else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0) & 0xF0FF);
-                } else {
-                    __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0) only
-                }
-                __builtin_amdgcn_sched_barrier(0);
-                lds_barrier();
-                __builtin_amdgcn_sched_barrier(0);
-                // -- compute phase
-                __builtin_amdgcn_s_setprio(1);
-#pragma unroll
-                for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-                    for (int i = 0; i < FM; ++i)
-#pragma unroll
-                        for (int j = 0; j < FN; ++j)
-                            acc[i][j] =
-                                __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk][j], af[kk][i], acc[i][j], 0, 0, 0);
-                __builtin_amdgcn_s_setprio(0);
-                __builtin_amdgcn_sched_barrier(0);
-                lds_barrier();
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-        if (grp == 0) lds_barrier();
+// Weight row behind row n of the block's B tile.  GEMM1: the wave tile's 32-column MFMA tiles alternate
+// W1 / W3 of the same 32 f columns.  Columns past N are clamped (never stored).
+template <int TN, bool SWIGLU>
+__device__ __forceinline__ const bf16_t* b_row_ptr(const GemmArgs& p, const Tile& t, int n)
+{
+    int col;
+    const bf16_t* W = t.Wa;
+    if (SWIGLU) {
+        const int w_n = n / TN, j = (n % TN) >> 5, c = n & 31;
+        col = t.n0 + (w_n * (TN / 64) + (j >> 1)) * 32 + c;
+        if (j & 1) W = t.Wb;
     } else {
-        for (int kt = 0; kt < nk; ++kt) {
-            // this wave's loads of tile kt have landed once at most the NSTAGE-2 younger tiles are outstanding
-            if (kt + NSTAGE - 2 < nk) __builtin_amdgcn_s_waitcnt(vmcnt_imm((NSTAGE - 2) * LD_PER_WAVE));
-            else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
-            lds_barrier();        // every wave's part of tile kt is in LDS; nobody still reads tile kt-1's buffer
-            if (kt + NSTAGE - 1 < nk) issue_loads(kt + NSTAGE - 1);
-            const char* St = smem + (kt % NSTAGE) * STAGE;
-#pragma unroll
-            for (int kk = 0; kk < KK; ++kk) {
-                const int sw = ((kk * 2 + (lane >> 5)) ^ swz) << 4;
-                bf16x8 af[FM], bfr[FN];
-#pragma unroll
-                for (int i = 0; i < FM; ++i) af[i] = *reinterpret_cast<const bf16x8*>(St + a_off + i * 32 * RB + sw);
-#pragma unroll
-                for (int j = 0; j < FN; ++j) bfr[j] = *reinterpret_cast<const bf16x8*>(St + b_off + j * 32 * RB + sw);
-#pragma unroll
-                for (int i = 0; i < FM; ++i)
-#pragma unroll
-                    for (int j = 0; j < FN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
-            }
-        }
+        col = t.n0 + n;
     }
+    col = col < p.N ? col : p.N - 1;
+    return W + (size_t)col * p.K;
+}
 
-    // ---- epilogue.  The MFMAs were issued as (weights x rows), so a lane holds, for output row lane&31,
-    // the four consecutive columns 8*(v>>2) + 4*(lane>>5) + 0..3 of each 32x32 tile: 8-byte bf16x4 stores.
-    unsigned short* out = reinterpret_cast<unsigned short*>(p.out);
+// Epilogue.  The MFMAs are issued as (weights x rows), so a lane holds, for output row lane&31, the four
+// consecutive columns 8*(v>>2) + 4*(lane>>5) + 0..3 of each 32x32 tile: SwiGLU in registers, 8-byte stores.
+template <int FM, int FN, int TM, int TN, bool SWIGLU>
+__device__ __forceinline__ void store_tile(const GemmArgs& p, const Tile& t, const f32x16 (&acc)[FM][FN], int wm,
+                                           int wn, int lane)
+{
+    unsigned short* out = reinterpret_cast<unsigned short*>(p.out) + (size_t)t.kslice * p.plane;
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
         const int rl = wm * TM + i * 32 + (lane & 31);
-        if (rl >= nrows) continue;
-        unsigned short* orow = out + (long)(row0 + rl) * p.ldo;
+        if (rl >= t.nrows) continue;
+        unsigned short* orow = out + (long)(t.row0 + rl) * p.ldo;
         if (SWIGLU) {
 #pragma unroll
             for (int jp = 0; jp < FN / 2; ++jp) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const int col = n0 + (wn * (TN / 64) + jp) * 32 + 8 * q + 4 * (lane >> 5);
+                    const int col = t.n0 + (wn * (TN / 64) + jp) * 32 + 8 * q + 4 * (lane >> 5);
                     unsigned short h[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
@@ -316,12 +200,12 @@ __global__ void __launch_bounds__(WM * WN * 64) ffn_gemm_kernel(GemmArgs p)
                 }
             }
         } else {
-            const float w = p.row_weight[row0 + rl];
+            const float w = p.row_weight[t.row0 + rl];
 #pragma unroll
             for (int j = 0; j < FN; ++j) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const int col = n0 + wn * TN + j * 32 + 8 * q + 4 * (lane >> 5);
+                    const int col = t.n0 + wn * TN + j * 32 + 8 * q + 4 * (lane >> 5);
                     unsigned short h[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) h[e] = f2bf(acc[i][j][4 * q + e] * w);
@@ -334,12 +218,228 @@ __global__ void __launch_bounds__(WM * WN * 64) ffn_gemm_kernel(GemmArgs p)
     }
 }
 
+// K slice of a block (ksplit > 1 only in GEMM2: partial sums go to separate planes of Y, which the
+// combine adds up in a fixed order).  Returns the first k tile and the number of k tiles.
+template <int BK>
+__device__ __forceinline__ void k_range(const GemmArgs& p, const Tile& t, int& k_first, int& nk)
+{
+    const int nk_all = p.K / BK;
+    const int nk_per = (nk_all + p.ksplit - 1) / p.ksplit;
+    k_first = t.kslice * nk_per;
+    nk = max(0, min(nk_all, k_first + nk_per) - k_first);
+}
+
+// LDS tile layout shared by both kernels.  A tile row holds BK bf16 = RB bytes = CPR 16-byte chunks.  The
+// LDS serves a ds_read_b128 sixteen lanes at a time across 64 banks (256 bytes = WR rows), so sixteen
+// consecutive rows reading the same chunk must fall on sixteen different 16-byte bank groups: chunk c of
+// row r is stored in slot c ^ ((r/WR) & (CPR-1)).  Tiles are filled by global_load_lds_dwordx4: one wave
+// instruction writes 1 KiB contiguously = RPG rows, lane l -> row l/CPR, slot l%CPR, so the swizzle is
+// applied to the global address each lane reads.
+template <int BK>
+struct Lds {
+    static constexpr int RB = BK * 2, CPR = RB / 16, WR = 256 / RB, RPG = 1024 / RB;
+    __device__ static __forceinline__ int lane_row(int lane) { return lane / CPR; }
+    __device__ static __forceinline__ int lane_chunk(int lane, int row) { return (lane % CPR) ^ ((row / WR) & (CPR - 1)); }
+    __device__ static __forceinline__ int read_swz(int lane) { return ((lane & 31) / WR) & (CPR - 1); }
+};
+
+// ------------------------------------------------------------------------------------------------
+// Small-tile kernel (4 waves, 32 or 64 rows): one ring of NSTAGE (A+B) stages, tiles kt+1..kt+NSTAGE-1 in
+// flight while tile kt is multiplied.  Used when experts hold few rows (decode): weight streaming bound.
+// ------------------------------------------------------------------------------------------------
+template <int BM, int BN, int WM, int WN, int BK, int NSTAGE, bool SWIGLU>
+__global__ void __launch_bounds__(WM * WN * 64) ffn_gemm_kernel(GemmArgs p)
+{
+    using L = Lds<BK>;
+    constexpr int TM = BM / WM, TN = BN / WN, FM = TM / 32, FN = TN / 32;
+    constexpr int RB = L::RB, RPG = L::RPG;
+    constexpr int STAGE = (BM + BN) * RB;
+    constexpr int NW = WM * WN;
+    constexpr int GROUPS = (BM + BN) / RPG;
+    constexpr int LD_PER_WAVE = GROUPS / NW;
+    static_assert(GROUPS % NW == 0, "loader shape");
+    static_assert(!SWIGLU || (FN % 2 == 0), "gate/up tiles must pair inside a wavefront");
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    Tile t;
+    if (!decode_tile<SWIGLU ? BN / 2 : BN, SWIGLU>(p, t)) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    int k_first, nk;
+    k_range<BK>(p, t, k_first, nk);
+
+    // wave w moves row groups w, w+NW, ... of every stage (A rows first, then B rows)
+    const bf16_t* gptr[LD_PER_WAVE];
+#pragma unroll
+    for (int i = 0; i < LD_PER_WAVE; ++i) {
+        const int row = (wave + i * NW) * RPG + L::lane_row(lane);
+        const bf16_t* base = row < BM ? a_row_ptr(p, t, row) : b_row_ptr<TN, SWIGLU>(p, t, row - BM);
+        gptr[i] = base + L::lane_chunk(lane, row) * 8 + (size_t)k_first * BK;
+    }
+    auto issue_loads = [&](int kt) {
+        char* dst = smem + (kt % NSTAGE) * STAGE + wave * 1024;
+#pragma unroll
+        for (int i = 0; i < LD_PER_WAVE; ++i)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gptr[i] + kt * BK),
+                                             (__attribute__((address_space(3))) void*)(dst + i * NW * 1024), 16, 0, 0);
+    };
+
+    f32x16 acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+#pragma unroll
+    for (int q = 0; q < NSTAGE - 1; ++q)
+        if (q < nk) issue_loads(q);
+    const int a_off = (wm * TM + (lane & 31)) * RB;
+    const int b_off = BM * RB + (wn * TN + (lane & 31)) * RB;
+    const int swz = L::read_swz(lane);
+    for (int kt = 0; kt < nk; ++kt) {
+        // this wave's loads of tile kt have landed once at most the NSTAGE-2 younger tiles are outstanding
+        if (kt + NSTAGE - 2 < nk) __builtin_amdgcn_s_waitcnt(vmcnt_imm((NSTAGE - 2) * LD_PER_WAVE));
+        else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+        lds_barrier();            // every wave's part of tile kt is in LDS; nobody still reads tile kt-1's buffer
+        if (kt + NSTAGE - 1 < nk) issue_loads(kt + NSTAGE - 1);
+        const char* St = smem + (kt % NSTAGE) * STAGE;
+#pragma unroll
+        for (int kk = 0; kk < BK / 16; ++kk) {
+            const int sw = ((kk * 2 + (lane >> 5)) ^ swz) << 4;
+            bf16x8 af[FM], bfr[FN];
+#pragma unroll
+            for (int i = 0; i < FM; ++i) af[i] = *reinterpret_cast<const bf16x8*>(St + a_off + i * 32 * RB + sw);
+#pragma unroll
+            for (int j = 0; j < FN; ++j) bfr[j] = *reinterpret_cast<const bf16x8*>(St + b_off + j * 32 * RB + sw);
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+        }
+    }
+    store_tile<FM, FN, TM, TN, SWIGLU>(p, t, acc, wm, wn, lane);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Large-tile kernel (BM x 256, 8 waves as 2 x 4), ping-pong: the two wave groups (wm = 0 / 1, one wave of
+// each per SIMD) run half a step out of phase, separated by barriers: while one group issues its 16
+// MFMAs for a 32-wide k step, the other reads its fragments of the next step from LDS and queues
+// global->LDS loads, so every SIMD's matrix pipe always has a wave feeding it.  Group 1 starts one
+// barrier late and group 0 ends one late.  k tiles of BK = 64 (full 128-byte lines per row), NSTAGE
+// LDS buffers; a tile is P = BK/32 steps.
+// ------------------------------------------------------------------------------------------------
+template <int BM, int BK, int NSTAGE, bool SWIGLU>
+__global__ void __launch_bounds__(512) ffn_gemm_pp_kernel(GemmArgs p)
+{
+    constexpr int BN = 256, WN = 4, NW = 8;
+    using L = Lds<BK>;
+    constexpr int TM = BM / 2, TN = BN / WN, FM = TM / 32, FN = TN / 32;
+    constexpr int RB = L::RB, RPG = L::RPG;
+    constexpr int STAGE = (BM + BN) * RB;
+    constexpr int GROUPS = (BM + BN) / RPG;
+    constexpr int LD_PER_WAVE = GROUPS / NW;
+    constexpr int P = BK / 32;
+    static_assert(GROUPS % NW == 0 && NSTAGE >= 2 && BK % 32 == 0, "loader shape");
+    static_assert(NSTAGE * STAGE <= 160 * 1024, "LDS budget of one CU");
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    Tile t;
+    if (!decode_tile<SWIGLU ? BN / 2 : BN, SWIGLU>(p, t)) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 2, wn = wave & 3;
+    const int grp = wm;
+    int k_first, nk;
+    k_range<BK>(p, t, k_first, nk);
+
+    const bf16_t* gptr[LD_PER_WAVE];
+#pragma unroll
+    for (int i = 0; i < LD_PER_WAVE; ++i) {
+        const int row = (wave + i * NW) * RPG + L::lane_row(lane);
+        const bf16_t* base = row < BM ? a_row_ptr(p, t, row) : b_row_ptr<TN, SWIGLU>(p, t, row - BM);
+        gptr[i] = base + L::lane_chunk(lane, row) * 8 + (size_t)k_first * BK;
+    }
+    auto issue_loads = [&](int kt) {
+        char* dst = smem + (kt % NSTAGE) * STAGE + wave * 1024;
+#pragma unroll
+        for (int i = 0; i < LD_PER_WAVE; ++i)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gptr[i] + kt * BK),
+                                             (__attribute__((address_space(3))) void*)(dst + i * NW * 1024), 16, 0, 0);
+    };
+
+    f32x16 acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+#pragma unroll
+    for (int q = 0; q < NSTAGE - 1; ++q)
+        if (q < nk) issue_loads(q);
+    const int a_off = (wm * TM + (lane & 31)) * RB;
+    const int b_off = BM * RB + (wn * TN + (lane & 31)) * RB;
+    const int swz = L::read_swz(lane);
+    if (NSTAGE - 2 < nk && NSTAGE > 2) __builtin_amdgcn_s_waitcnt(vmcnt_imm((NSTAGE - 2) * LD_PER_WAVE));
+    else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    lds_barrier();                                        // tile 0 is in LDS for everyone
+    if (grp == 1) lds_barrier();
+    for (int kt = 0; kt < nk; ++kt) {
+        const char* St = smem + (kt % NSTAGE) * STAGE;
+#pragma unroll
+        for (int ph = 0; ph < P; ++ph) {
+            // -- memory phase.  At the first step of tile kt the buffer of tile kt-1 is free (both groups
+            // finished reading it two barriers ago): refill it with tile kt+NSTAGE-1.
+            if (ph == 0 && kt + NSTAGE - 1 < nk) issue_loads(kt + NSTAGE - 1);
+            bf16x8 af[2][FM], bfr[2][FN];
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk) {
+                const int sw = (((ph * 2 + kk) * 2 + (lane >> 5)) ^ swz) << 4;
+#pragma unroll
+                for (int i = 0; i < FM; ++i) af[kk][i] = *reinterpret_cast<const bf16x8*>(St + a_off + i * 32 * RB + sw);
+#pragma unroll
+                for (int j = 0; j < FN; ++j) bfr[kk][j] = *reinterpret_cast<const bf16x8*>(St + b_off + j * 32 * RB + sw);
+            }
+            // fragments are in registers (lgkmcnt 0); at the last step of tile kt, tile kt+1 must have
+            // landed too: it is read right after the next barrier pair
+            if (ph == P - 1) {
+                if (NSTAGE > 2 && kt + NSTAGE - 1 < nk)
+                    __builtin_amdgcn_s_waitcnt(vmcnt_lgkm0_imm((NSTAGE - 2) * LD_PER_WAVE));
+                else __builtin_amdgcn_s_waitcnt(vmcnt_lgkm0_imm(0));
+            } else {
+                __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0) only
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            lds_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            // -- compute phase
+            __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+                for (int i = 0; i < FM; ++i)
+#pragma unroll
+                    for (int j = 0; j < FN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk][j], af[kk][i], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_s_setprio(0);
+            __builtin_amdgcn_sched_barrier(0);
+            lds_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    if (grp == 0) lds_barrier();
+    store_tile<FM, FN, TM, TN, SWIGLU>(p, t, acc, wm, wn, lane);
+}
+
 // ------------------------------------------------------------------------------------------------
 // combine: one thread = 8 columns of one token; rows summed in slot order, shared experts first.
 // ------------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) combine_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ Y,
                                                       const int32_t* __restrict__ token_rows, bf16_t* __restrict__ out,
-                                                      int T, int d, int K, int Ns, int add_residual)
+                                                      int T, int d, int K, int Ns, int add_residual, int ksplit, long plane)
 {
     const int chunks = d >> 3;
     const long gid = (long)blockIdx.x * 256 + threadIdx.x;
@@ -360,10 +460,12 @@ __global__ void __launch_bounds__(256) combine_kernel(const bf16_t* __restrict__
     if (add_residual) add_row(x + (long)t * d);
     const int slots = K + Ns;
     const int32_t* tr = token_rows + (long)t * slots;
-    for (int s = 0; s < Ns; ++s) add_row(Y + (long)tr[K + s] * d);
+    for (int s = 0; s < Ns; ++s)
+        for (int q = 0; q < ksplit; ++q) add_row(Y + q * plane + (long)tr[K + s] * d);
     for (int j = 0; j < K; ++j) {
         const int r = tr[j];
-        if (r >= 0) add_row(Y + (long)r * d);
+        if (r >= 0)
+            for (int q = 0; q < ksplit; ++q) add_row(Y + q * plane + (long)r * d);
     }
     uint4 o;
     o.x = (unsigned)f2bf(acc[0]) | ((unsigned)f2bf(acc[1]) << 16);
@@ -374,47 +476,50 @@ __global__ void __launch_bounds__(256) combine_kernel(const bf16_t* __restrict__
 }
 
 // ------------------------------------------------------------------------------------------------
-template <int BM, int BN, int WM, int WN, int BK, int NSTAGE, bool PINGPONG, bool SWIGLU>
-static hipError_t launch_gemm(const GemmArgs& a, int max_mtiles, hipStream_t s)
+template <typename Kern>
+static hipError_t launch_tiles(Kern kern, bool& attr_set, int threads, int lds, int bn_cols, GemmArgs a, int max_mtiles,
+                               hipStream_t s)
 {
-    constexpr int NTH = WM * WN * 64;
-    constexpr int LDS = NSTAGE * (BM + BN) * BK * 2;
-    static_assert(LDS <= 160 * 1024, "LDS budget of one CU");
-    static bool attr_set = false;
-    auto kern = ffn_gemm_kernel<BM, BN, WM, WN, BK, NSTAGE, PINGPONG, SWIGLU>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const long total = (long)max_mtiles * a.n_ntiles;
+    a.n_ntiles = ceil_div(a.N, bn_cols);
+    const long total = (long)max_mtiles * a.n_ntiles * a.ksplit;
     const int grid = (int)((total + 7) / 8 * 8);
-    kern<<<grid, NTH, LDS, s>>>(a);
+    kern<<<grid, threads, lds, s>>>(a);
     return hipGetLastError();
 }
 
-// Tile height from the expected rows per unit (the counts themselves stay on the device).
-static int pick_bm(int64_t expected_rows_per_unit)
+template <int BM, int BN, int WM, int WN, int BK, int NSTAGE, bool SWIGLU>
+static hipError_t launch_small(const GemmArgs& a, int max_mtiles, hipStream_t s)
 {
-    if (const char* e = std::getenv("BROWNOUT_MOE_BM")) {
-        const int v = std::atoi(e);
-        if (v == 32 || v == 64 || v == 128 || v == 256) return v;
-    }
-    if (expected_rows_per_unit >= 384) return 256;
-    if (expected_rows_per_unit >= 96) return 128;
-    if (expected_rows_per_unit >= 40) return 64;
-    return 32;
+    constexpr int LDS = NSTAGE * (BM + BN) * BK * 2;
+    static_assert(LDS <= 160 * 1024, "LDS budget of one CU");
+    static bool attr_set = false;
+    return launch_tiles(ffn_gemm_kernel<BM, BN, WM, WN, BK, NSTAGE, SWIGLU>, attr_set, WM * WN * 64, LDS,
+                        SWIGLU ? BN / 2 : BN, a, max_mtiles, s);
+}
+
+template <int BM, int BK, int NSTAGE, bool SWIGLU>
+static hipError_t launch_pp(const GemmArgs& a, int max_mtiles, hipStream_t s)
+{
+    constexpr int LDS = NSTAGE * (BM + 256) * BK * 2;
+    static bool attr_set = false;
+    return launch_tiles(ffn_gemm_pp_kernel<BM, BK, NSTAGE, SWIGLU>, attr_set, 512, LDS, SWIGLU ? 128 : 256, a, max_mtiles,
+                        s);
 }
 
 template <bool SWIGLU>
 static hipError_t dispatch_gemm(int BM, const GemmArgs& a, int max_mtiles, hipStream_t s)
 {
     switch (BM) {
-        case 256: return launch_gemm<256, 256, 2, 4, 64, 2, true, SWIGLU>(a, max_mtiles, s);
-        case 128: return launch_gemm<128, 256, 2, 4, 64, 3, true, SWIGLU>(a, max_mtiles, s);
-        case 64: return launch_gemm<64, 256, 1, 4, 64, 3, false, SWIGLU>(a, max_mtiles, s);
-        default: return launch_gemm<32, 256, 1, 4, 64, 4, false, SWIGLU>(a, max_mtiles, s);
+        case 256: return launch_pp<256, 64, 2, SWIGLU>(a, max_mtiles, s);
+        case 128: return launch_pp<128, 64, 3, SWIGLU>(a, max_mtiles, s);
+        case 64: return launch_small<64, 256, 1, 4, 64, 3, SWIGLU>(a, max_mtiles, s);
+        default: return launch_small<32, 256, 1, 4, 64, 4, SWIGLU>(a, max_mtiles, s);
     }
 }
 
@@ -424,7 +529,7 @@ hipError_t launch_ffn(const Dims& D, int u_lo, int u_hi, int Fdim, int64_t expec
                       const FfnWeights& shared, int32_t* tile_table, bf16_t* H, bf16_t* Y, hipStream_t s)
 {
     const int n_units = u_hi - u_lo;
-    const int BM = pick_bm(expected_rows);
+    const int BM = pick_tile_rows(expected_rows);
     const int max_mtiles = (int)std::min<int64_t>(D.row_cap / BM + n_units, D.tile_cap);
     {
         ProfScope ps(MOE_STAGE_TILES, s);
@@ -436,10 +541,11 @@ hipError_t launch_ffn(const Dims& D, int u_lo, int u_hi, int Fdim, int64_t expec
     g1.wb0 = experts.w3; g1.wb1 = united.w3; g1.wb2 = shared.w3;
     g1.m = D.m; g1.G = D.G; g1.N = Fdim; g1.K = D.d;
     g1.out = H; g1.ldo = D.Fmax; g1.row_weight = nullptr;
-    g1.n_ntiles = ceil_div(Fdim, 128);
+    g1.n_ntiles = 0;                            // set by launch_gemm from its tile width
     int group_m = 4;
     if (const char* e = std::getenv("BROWNOUT_MOE_GM")) group_m = std::max(1, std::atoi(e));
     g1.group_m = group_m;
+    g1.ksplit = 1; g1.plane = 0;
     {
         ProfScope ps(MOE_STAGE_GEMM1, s);
         hipError_t e = dispatch_gemm<true>(BM, g1, max_mtiles, s);
@@ -451,8 +557,9 @@ hipError_t launch_ffn(const Dims& D, int u_lo, int u_hi, int Fdim, int64_t expec
     g2.wb0 = g2.wb1 = g2.wb2 = nullptr;
     g2.m = D.m; g2.G = D.G; g2.N = D.d; g2.K = Fdim;
     g2.out = Y; g2.ldo = D.d; g2.row_weight = row_weight;
-    g2.n_ntiles = ceil_div(D.d, 256);
+    g2.n_ntiles = 0;
     g2.group_m = group_m;
+    g2.ksplit = D.ksplit; g2.plane = D.y_plane;
     {
         ProfScope ps(MOE_STAGE_GEMM2, s);
         hipError_t e = dispatch_gemm<false>(BM, g2, max_mtiles, s);
@@ -466,7 +573,8 @@ hipError_t launch_combine(const Dims& D, const bf16_t* x, const bf16_t* Y, const
 {
     ProfScope ps(MOE_STAGE_COMBINE, s);
     const long n = (long)D.T * (D.d / 8);
-    combine_kernel<<<(int)((n + 255) / 256), 256, 0, s>>>(x, Y, token_rows, out, D.T, D.d, D.K, D.Ns, D.add_residual);
+    combine_kernel<<<(int)((n + 255) / 256), 256, 0, s>>>(x, Y, token_rows, out, D.T, D.d, D.K, D.Ns, D.add_residual,
+                                                          D.ksplit, D.y_plane);
     return hipGetLastError();
 }
 

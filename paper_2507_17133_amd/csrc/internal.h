@@ -28,8 +28,12 @@ struct Dims {
     int64_t row_cap;   // rows the row lists can hold: T*(K+Ns)
     int n_seg;         // routing segments
     int tile_cap;      // entries of one GEMM tile table
+    int ksplit;        // K slices of GEMM2 (partial products in separate planes of Y)
+    int64_t y_plane;   // elements between two planes of Y
 };
 Dims make_dims(const moe_config& c, int T);
+// GEMM tile height from the expected rows per expert (the real counts stay on the device).
+int pick_tile_rows(int64_t expected_rows_per_unit);
 
 // Carving of the caller's workspace.  All offsets are multiples of 256 bytes.
 struct Workspace {
