@@ -49,8 +49,10 @@ int pick_tile_rows(int64_t expected_rows_per_unit)
         if (v == 32 || v == 64 || v == 128 || v == 256) return v;
     }
     if (expected_rows_per_unit >= 384) return 256;
-    if (expected_rows_per_unit >= 96) return 128;
-    if (expected_rows_per_unit >= 40) return 64;
+    // one tile should hold an expert's rows with room for the spread around the mean: a second, nearly
+    // empty tile would stream the expert's weights a second time
+    if (expected_rows_per_unit >= 48) return 128;
+    if (expected_rows_per_unit >= 24) return 64;
     return 32;
 }
 

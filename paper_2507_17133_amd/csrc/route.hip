@@ -9,6 +9,8 @@
 // No floating-point atomics anywhere; integer atomics only where the result does not depend on order.
 #include "internal.h"
 
+#include <algorithm>
+
 namespace bmoe {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -48,8 +50,10 @@ __global__ void __launch_bounds__(256) prep_kernel(const float* __restrict__ gat
 }
 
 // ------------------------------------------------------------------------------------------------
-// gate: one block = 16 tokens x all experts.  Four wavefronts share the (expert tile, k slice) space:
-// NG = min(4, m_pad/16) expert groups of NTW 16-wide tiles, 4/NG k slices.  Each 64-wide k chunk is
+// gate: one block = 16 tokens x all experts.  Sixteen wavefronts share the (expert tile, k slice) space:
+// NG = min(4, m_pad/16) expert groups of NTW 16-wide tiles, KS k slices (as many as 16/NG and the
+// 256 partial sums per token of the LDS exchange allow): a wave's bandwidth is bounded by the few loads
+// it keeps in flight, so short slices in many waves are what makes a small batch fast.  Each 64-wide k chunk is
 // accumulated from zero by six 16x16x32 bf16 MFMAs (lo, mid, hi pieces) and folded into an fp64 running
 // sum, which keeps the logit within a few 1e-8 of the exact dot product whatever d is.
 // ------------------------------------------------------------------------------------------------
@@ -59,8 +63,62 @@ struct GateArgs {
     int32_t* topk_idx; float* topk_w; int32_t* expert_cnt; uint8_t* near_tie;
 };
 
+// TopK(.,K) of one token by one wavefront: lane holds experts lane, lane+64, ...; K (+1 for the best
+// loser) rounds of "best of my candidates, then best across lanes" (higher score, equal scores: lower
+// id); lane j keeps the j-th winner, weights are normalised over lanes 0..K-1.
+__device__ __forceinline__ void topk_token(const GateArgs& p, const float* logit_row, int t, int lane, int* hist)
+{
+    const int K = p.K;
+    const int n_pick = K < p.m ? K + 1 : K;    // one extra pick: the best loser, for the near-tie flag
+    float v[4];
+    unsigned taken = 0;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const int e = lane + 64 * c;
+        v[c] = e < p.m ? logit_row[e] : 0.0f;
+        if (e >= p.m) taken |= 1u << c;
+    }
+    float my_v = 0.0f;
+    int my_i = 0;
+    for (int j = 0; j < n_pick; ++j) {
+        float bv = 0.0f;
+        int bi = 0x7fffffff;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (taken & (1u << c)) continue;
+            if (bi == 0x7fffffff || v[c] > bv) { bv = v[c]; bi = lane + 64 * c; }
+        }
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const float ov = __shfl_xor(bv, off);
+            const int oi = __shfl_xor(bi, off);
+            const bool take = oi != 0x7fffffff && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi));
+            if (take) { bv = ov; bi = oi; }
+        }
+        bv = __shfl(bv, 0);
+        bi = __shfl(bi, 0);
+        if ((bi & 63) == lane) taken |= 1u << (bi >> 6);
+        if (lane == j) { my_v = bv; my_i = bi; }
+    }
+    const float top = __shfl(my_v, 0);
+    float num = 0.0f;
+    if (lane < K) num = p.score_fn == 0 ? expf(my_v - top) : 1.0f / (1.0f + expf(-my_v));
+    float den = num;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) den += __shfl_xor(den, off);
+    const float nxt = __shfl_down(my_v, 1);
+    const bool close = lane + 1 < n_pick && (my_v - nxt) < 1e-6f;
+    const unsigned long long any_close = __ballot(close);
+    if (lane < K) {
+        p.topk_idx[(size_t)t * K + lane] = my_i;
+        p.topk_w[(size_t)t * K + lane] = num / den;
+        atomicAdd(&hist[my_i], 1);
+    }
+    if (lane == 0 && p.near_tie != nullptr) p.near_tie[t] = any_close != 0ull ? 1 : 0;
+}
+
 template <int NTW>
-__global__ void __launch_bounds__(256) gate_topk_kernel(GateArgs p)
+__global__ void __launch_bounds__(1024) gate_topk_kernel(GateArgs p)
 {
     __shared__ double part[16 * kMaxExperts];   // [ks][token][m_pad], KS*m_pad <= 256
     __shared__ float logit[16 * kMaxExperts];   // [token][m_pad]
@@ -69,7 +127,7 @@ __global__ void __launch_bounds__(256) gate_topk_kernel(GateArgs p)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int t0 = blockIdx.x * 16;
     const int n_tiles = p.m_pad >> 4;
-    for (int i = tid; i < p.m_pad; i += 256) hist[i] = 0;
+    for (int i = tid; i < p.m_pad; i += 1024) hist[i] = 0;
 
     const bool active = wave < p.NG * p.KS;
     const int ng = wave % p.NG, ks = wave / p.NG;
@@ -97,12 +155,46 @@ __global__ void __launch_bounds__(256) gate_topk_kernel(GateArgs p)
 #pragma unroll
             for (int v = 0; v < 4; ++v) sum[nt][v] = 0.0;
         }
-        for (int kstep = k_lo; kstep < k_hi; ++kstep) {
+        // UNR k steps per round trip: all their fragments are requested before the first MFMA, so a wave
+        // pays the memory latency once per UNR*32 k instead of once per 32
+        constexpr int UNR = NTW == 1 ? 8 : (NTW == 2 ? 4 : 2);
+        int kstep = k_lo;
+        for (; kstep + UNR <= k_hi; kstep += UNR) {
+            bf16x8 a[UNR], b[UNR][NTW][3];
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) {
+                const int ko = (kstep + u) << 5;
+                a[u] = *reinterpret_cast<const bf16x8*>(ap + ko);
+#pragma unroll
+                for (int nt = 0; nt < NTW; ++nt) {
+#pragma unroll
+                    for (int pz = 0; pz < 3; ++pz)
+                        b[u][nt][pz] = *reinterpret_cast<const bf16x8*>(bp[nt] + pz * piece + ko);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < UNR; ++u) {
+#pragma unroll
+                for (int nt = 0; nt < NTW; ++nt) {
+                    acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u], b[u][nt][2], acc[nt], 0, 0, 0);
+                    acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u], b[u][nt][1], acc[nt], 0, 0, 0);
+                    acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u], b[u][nt][0], acc[nt], 0, 0, 0);
+                }
+                if (u & 1) {
+#pragma unroll
+                    for (int nt = 0; nt < NTW; ++nt) {
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) sum[nt][v] += (double)acc[nt][v];
+                        acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    }
+                }
+            }
+        }
+        for (; kstep < k_hi; ++kstep) {
             const int ko = kstep << 5;
             const bf16x8 a = *reinterpret_cast<const bf16x8*>(ap + ko);
 #pragma unroll
             for (int nt = 0; nt < NTW; ++nt) {
-                if (!tile_ok[nt]) continue;
                 const bf16x8 b_lo = *reinterpret_cast<const bf16x8*>(bp[nt] + 2 * piece + ko);
                 const bf16x8 b_mid = *reinterpret_cast<const bf16x8*>(bp[nt] + piece + ko);
                 const bf16x8 b_hi = *reinterpret_cast<const bf16x8*>(bp[nt] + ko);
@@ -110,13 +202,11 @@ __global__ void __launch_bounds__(256) gate_topk_kernel(GateArgs p)
                 acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_mid, acc[nt], 0, 0, 0);
                 acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_hi, acc[nt], 0, 0, 0);
             }
-            if (((kstep - k_lo) & 1) == 1 || kstep + 1 == k_hi) {
 #pragma unroll
-                for (int nt = 0; nt < NTW; ++nt) {
+            for (int nt = 0; nt < NTW; ++nt) {
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) sum[nt][v] += (double)acc[nt][v];
-                    acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-                }
+                for (int v = 0; v < 4; ++v) sum[nt][v] += (double)acc[nt][v];
+                acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
         }
         // MFMA 16x16 result layout: lane holds column (lane&15) = expert, rows 4*(lane>>4)+v = tokens.
@@ -132,7 +222,7 @@ __global__ void __launch_bounds__(256) gate_topk_kernel(GateArgs p)
         }
     }
     __syncthreads();
-    for (int i = tid; i < 16 * p.m_pad; i += 256) {
+    for (int i = tid; i < 16 * p.m_pad; i += 1024) {
         const int tok = i / p.m_pad, e = i - tok * p.m_pad;
         double s = 0.0;
         for (int q = 0; q < p.KS; ++q) s += part[(q * 16 + tok) * p.m_pad + e];
@@ -141,62 +231,125 @@ __global__ void __launch_bounds__(256) gate_topk_kernel(GateArgs p)
     }
     __syncthreads();
 
-    // TopK: each wavefront takes 4 tokens; lane holds experts lane, lane+64, ...
-    const int K = p.K;
-    const int n_pick = K < p.m ? K + 1 : K;    // one extra pick: the best loser, for the near-tie flag
-    for (int q = 0; q < 4; ++q) {
-        const int tok = wave * 4 + q;
-        const int t = t0 + tok;
-        if (t >= p.T) break;
-        float v[4];
-        unsigned taken = 0;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const int e = lane + 64 * c;
-            v[c] = e < p.m ? logit[tok * p.m_pad + e] : 0.0f;
-            if (e >= p.m) taken |= 1u << c;
+    // TopK: one token per wavefront
+    if (t0 + wave < p.T) topk_token(p, logit + wave * p.m_pad, t0 + wave, lane, hist);
+    __syncthreads();
+    for (int i = tid; i < p.m; i += 1024)
+        if (hist[i] > 0) atomicAdd(&p.expert_cnt[i], hist[i]);
+}
+
+// ------------------------------------------------------------------------------------------------
+// gate for many experts and many tokens: one block = 16*TG tokens x all experts, 2*TG wavefronts
+// (token group tg = wave % TG, expert half eh = wave / TG).  The three weight pieces of a 32-wide k
+// step ([3][m_pad] rows of 64 bytes) are staged in LDS by global_load_lds_dwordx4 (3 stages) and read
+// together with the block's x rows and read by every wave, so the split gate matrix is fetched once per
+// 16*TG tokens instead of once per 16.  Same arithmetic as gate_topk_kernel.
+// ------------------------------------------------------------------------------------------------
+template <int TG, int NTH>
+__global__ void __launch_bounds__(TG * 128) gate_tiled_kernel(GateArgs p)
+{
+    constexpr int NWV = 2 * TG, NST = 3;
+    extern __shared__ __attribute__((aligned(16))) char gsm[];
+    __shared__ int hist[kMaxExperts];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tg = wave % TG, eh = wave / TG;
+    const int t0 = blockIdx.x * (16 * TG);
+    const int n_tiles = p.m_pad >> 4;
+    const int w_rows = 3 * p.m_pad;                     // LDS rows of one stage: [piece][expert], then the x rows
+    const int rows = w_rows + 16 * TG;
+    const int groups = rows >> 4;                       // 16 rows (1 KiB) per wave-wide load
+    const int stage_bytes = rows * 64;
+    for (int i = tid; i < p.m_pad; i += TG * 128) hist[i] = 0;
+
+    // loader: wave w moves row groups w, w+NWV, ...; lane -> row lane/4, 16-byte slot lane%4 holding
+    // chunk (lane%4) ^ ((row/4)&3)  (conflict-free ds_read_b128 on the 64-bank LDS)
+    const int ksteps = p.d >> 5;
+    auto issue = [&](int ks) {
+        char* dst = gsm + (ks % NST) * stage_bytes;
+        for (int g = wave; g < groups; g += NWV) {
+            const int row = g * 16 + (lane >> 2);
+            const int chunk = (lane & 3) ^ ((row >> 2) & 3);
+            const unsigned short* src;
+            if (row < w_rows) src = p.split + (size_t)row * p.d;
+            else src = reinterpret_cast<const unsigned short*>(p.x) + (size_t)min(t0 + row - w_rows, p.T - 1) * p.d;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + (ks << 5) + chunk * 8),
+                                             (__attribute__((address_space(3))) void*)(dst + g * 1024), 16, 0, 0);
         }
-        float my_v = 0.0f;
-        int my_i = 0;
-        for (int j = 0; j < n_pick; ++j) {
-            float bv = 0.0f;
-            int bi = 0x7fffffff;
+    };
+
+    double sum[NTH][4];
+    f32x4 acc[NTH];
+    bool tile_ok[NTH];
+    int boff[NTH];
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                if (taken & (1u << c)) continue;
-                if (bi == 0x7fffffff || v[c] > bv) { bv = v[c]; bi = lane + 64 * c; }
+    for (int nt = 0; nt < NTH; ++nt) {
+        const int tile = eh * NTH + nt;
+        tile_ok[nt] = tile < n_tiles;
+        const int erow = (tile_ok[nt] ? tile : 0) * 16 + (lane & 15);
+        boff[nt] = erow * 64 + (((lane >> 4) ^ ((erow >> 2) & 3)) << 4);
+        acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int v = 0; v < 4; ++v) sum[nt][v] = 0.0;
+    }
+    const int arow = w_rows + tg * 16 + (lane & 15);
+    const int aoff = arow * 64 + (((lane >> 4) ^ ((arow >> 2) & 3)) << 4);
+    // All loads of the loop go to LDS and complete in order per wave: at the top of step ks the loads of
+    // stage ks are older than the `young` loads of stage ks+1, which may stay in flight.
+    const int young = groups / NWV;                     // loads of one stage every wave issues at least
+    issue(0);
+    if (ksteps > 1) issue(1);
+    for (int ks = 0; ks < ksteps; ++ks) {
+        if (ks + 1 >= ksteps) __builtin_amdgcn_s_waitcnt(0x0F70);
+        else if (young >= 6) __builtin_amdgcn_s_waitcnt(0x0F76);
+        else if (young >= 3) __builtin_amdgcn_s_waitcnt(0x0F73);
+        else if (young >= 2) __builtin_amdgcn_s_waitcnt(0x0F72);
+        else if (young >= 1) __builtin_amdgcn_s_waitcnt(0x0F71);
+        else __builtin_amdgcn_s_waitcnt(0x0F70);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();                   // stage ks is in LDS for everyone; stage ks-1 is free
+        asm volatile("" ::: "memory");
+        if (ks + 2 < ksteps) issue(ks + 2);
+        const char* St = gsm + (ks % NST) * stage_bytes;
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(St + aoff);
+#pragma unroll
+        for (int nt = 0; nt < NTH; ++nt) {
+            const bf16x8 b_hi = *reinterpret_cast<const bf16x8*>(St + boff[nt]);
+            const bf16x8 b_mid = *reinterpret_cast<const bf16x8*>(St + p.m_pad * 64 + boff[nt]);
+            const bf16x8 b_lo = *reinterpret_cast<const bf16x8*>(St + 2 * p.m_pad * 64 + boff[nt]);
+            acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_lo, acc[nt], 0, 0, 0);
+            acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_mid, acc[nt], 0, 0, 0);
+            acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_hi, acc[nt], 0, 0, 0);
+        }
+        if ((ks & 1) == 1 || ks + 1 == ksteps) {
+#pragma unroll
+            for (int nt = 0; nt < NTH; ++nt) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) sum[nt][v] += (double)acc[nt][v];
+                acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) {
-                const float ov = __shfl_xor(bv, off);
-                const int oi = __shfl_xor(bi, off);
-                const bool take = oi != 0x7fffffff && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi));
-                if (take) { bv = ov; bi = oi; }
-            }
-            bv = __shfl(bv, 0);
-            bi = __shfl(bi, 0);
-            if ((bi & 63) == lane) taken |= 1u << (bi >> 6);
-            if (lane == j) { my_v = bv; my_i = bi; }
         }
-        // weights over lanes 0..K-1
-        const float top = __shfl(my_v, 0);
-        float num = 0.0f;
-        if (lane < K) num = p.score_fn == 0 ? expf(my_v - top) : 1.0f / (1.0f + expf(-my_v));
-        float den = num;
+    }
+    __syncthreads();                                    // every wave is done with the stages: reuse as logits
+    float* logit = reinterpret_cast<float*>(gsm);       // [16*TG][m_pad]
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) den += __shfl_xor(den, off);
-        const float nxt = __shfl_down(my_v, 1);
-        const bool close = lane + 1 < n_pick && (my_v - nxt) < 1e-6f;
-        const unsigned long long any_close = __ballot(close);
-        if (lane < K) {
-            p.topk_idx[(size_t)t * K + lane] = my_i;
-            p.topk_w[(size_t)t * K + lane] = num / den;
-            atomicAdd(&hist[my_i], 1);
+    for (int nt = 0; nt < NTH; ++nt) {
+        if (!tile_ok[nt]) continue;
+        const int e = (eh * NTH + nt) * 16 + (lane & 15);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int tok = tg * 16 + 4 * (lane >> 4) + v;
+            double s = sum[nt][v];
+            if (p.bias != nullptr && e < p.m) s += (double)p.bias[e];
+            logit[tok * p.m_pad + e] = (float)s;
         }
-        if (lane == 0 && p.near_tie != nullptr) p.near_tie[t] = any_close != 0ull ? 1 : 0;
     }
     __syncthreads();
-    for (int i = tid; i < p.m; i += 256)
+    for (int tok = wave; tok < 16 * TG; tok += NWV) {
+        if (t0 + tok >= p.T) break;
+        topk_token(p, logit + tok * p.m_pad, t0 + tok, lane, hist);
+    }
+    __syncthreads();
+    for (int i = tid; i < p.m; i += TG * 128)
         if (hist[i] > 0) atomicAdd(&p.expert_cnt[i], hist[i]);
 }
 
@@ -395,13 +548,44 @@ hipError_t launch_route(const Dims& D, const bf16_t* x, const float* gate_w, con
         g.T = D.T; g.d = D.d; g.m = D.m; g.m_pad = D.m_pad; g.K = D.K; g.score_fn = D.score_fn;
         const int n_tiles = D.m_pad / 16;
         g.NG = n_tiles < 4 ? n_tiles : 4;
-        g.KS = 4 / g.NG;
+        g.KS = std::max(1, std::min(16 / g.NG, 256 / D.m_pad));
         const int ntw = ceil_div(n_tiles, g.NG);
         g.topk_idx = R.topk_idx; g.topk_w = R.topk_w; g.expert_cnt = R.expert_cnt; g.near_tie = R.near_tie;
-        const int blocks = ceil_div(D.T, 16);
-        if (ntw == 1) gate_topk_kernel<1><<<blocks, 256, 0, s>>>(g);
-        else if (ntw == 2) gate_topk_kernel<2><<<blocks, 256, 0, s>>>(g);
-        else gate_topk_kernel<4><<<blocks, 256, 0, s>>>(g);
+        // many experts and enough tokens to fill the CUs with wider token tiles: LDS-staged variant
+        const int half_tiles = ceil_div(n_tiles, 2);
+        const int tgw = D.T >= 64 * 192 ? 4 : (D.T >= 32 * 192 ? 2 : 0);
+        if (n_tiles >= 4 && tgw != 0) {
+            const int lds = std::max(3 * (3 * D.m_pad + 16 * tgw) * 64, 16 * tgw * D.m_pad * 4);
+            const int blocks = ceil_div(D.T, 16 * tgw);
+            hipError_t e = hipSuccess;
+#define BMOE_GATE_TILED(TG_, NTH_)                                                                               \
+            do {                                                                                                   \
+                static bool attr_set = false;                                                                      \
+                if (!attr_set) {                                                                                   \
+                    e = hipFuncSetAttribute(reinterpret_cast<const void*>(gate_tiled_kernel<TG_, NTH_>),           \
+                                            hipFuncAttributeMaxDynamicSharedMemorySize,                            \
+                                            3 * (3 * kMaxExperts + 16 * TG_) * 64);                                \
+                    attr_set = e == hipSuccess;                                                                    \
+                }                                                                                                  \
+                if (e == hipSuccess) gate_tiled_kernel<TG_, NTH_><<<blocks, TG_ * 128, lds, s>>>(g);               \
+            } while (0)
+            if (tgw == 4) {
+                if (half_tiles <= 2) BMOE_GATE_TILED(4, 2);
+                else if (half_tiles <= 4) BMOE_GATE_TILED(4, 4);
+                else BMOE_GATE_TILED(4, 8);
+            } else {
+                if (half_tiles <= 2) BMOE_GATE_TILED(2, 2);
+                else if (half_tiles <= 4) BMOE_GATE_TILED(2, 4);
+                else BMOE_GATE_TILED(2, 8);
+            }
+#undef BMOE_GATE_TILED
+            if (e != hipSuccess) return e;
+        } else {
+            const int blocks = ceil_div(D.T, 16);
+            if (ntw == 1) gate_topk_kernel<1><<<blocks, 1024, 0, s>>>(g);
+            else if (ntw == 2) gate_topk_kernel<2><<<blocks, 1024, 0, s>>>(g);
+            else gate_topk_kernel<4><<<blocks, 1024, 0, s>>>(g);
+        }
     }
     RowArgs p;
     p.topk_idx = R.topk_idx; p.topk_w = R.topk_w; p.expert_cnt = R.expert_cnt;

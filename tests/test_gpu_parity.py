@@ -41,6 +41,10 @@ SMALL = {
                                           F_s=64), [1.0, 0.5]),
     "sixty_experts_way8": (WL.LayerConfig("sixty", T=260, d=128, F=64, m=60, K=4, way=8, zipf_s=1.0), [0.4]),
     "way_above_m": (WL.LayerConfig("way_above_m", T=90, d=64, F=64, m=5, K=2, way=16), [0.5]),
+    "tiled_gate_2groups": (WL.LayerConfig("tiled_gate_2groups", T=6200, d=128, F=64, m=96, K=4, way=8, zipf_s=1.0),
+                           [0.5]),
+    "tiled_gate_4groups": (WL.LayerConfig("tiled_gate_4groups", T=12500, d=64, F=64, m=60, K=3, way=8, score_fn=1),
+                           [1.0, 0.3]),
     "mid_tile": (WL.LayerConfig("mid_tile", T=600, d=128, F=256, m=8, K=2, way=4), [1.0, 0.5]),
     "multi_tile": (WL.LayerConfig("multi_tile", T=1500, d=256, F=384, m=4, K=2, way=4, zipf_s=1.2), [1.0, 0.7]),
 }
