@@ -1,6 +1,7 @@
 // C ABI of libbrownout_moe.so: argument validation, workspace carving, kernel sequencing, profiling.
 #include "internal.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -32,11 +33,13 @@ Dims make_dims(const moe_config& c, int T)
     D.row_cap = (int64_t)T * D.slots;
     D.n_seg = ceil_div(T, kSegTokens);
     D.tile_cap = (int)(D.row_cap / kMinTileRows) + D.U;
-    // GEMM2 has few, long tiles (N = d): split K until about six rounds of blocks fill the 256 CUs.
+    // GEMM2 has few, long tiles (N = d): split K (at most 4 ways) until about four rounds of blocks fill
+    // the 256 CUs; more slices only add prologues and planes for the combine to sum.
     const int bm = pick_tile_rows((int64_t)T * D.K / D.m);
     const int64_t tiles2 = (D.row_cap / bm + (D.m + D.G) / 2 + D.Ns) * (int64_t)ceil_div(D.d, 256);
     int ks = 1;
-    while (ks < 8 && tiles2 * ks < 1536 && (D.F / 64) / (ks * 2) >= 8) ks *= 2;
+    while (ks < 4 && tiles2 * ks < 1024 && (D.F / 64) / (ks * 2) >= 8) ks *= 2;
+    if (const char* e = std::getenv("BROWNOUT_MOE_KSPLIT")) ks = std::max(1, std::min(8, std::atoi(e)));
     D.ksplit = ks;
     D.y_plane = D.row_cap * (int64_t)D.d;
     return D;
