@@ -4,7 +4,7 @@
 //            wavefront shuffles, weights g, expert histogram        (Architecture of BrownoutMoE)
 //   count    Algorithm 1's S1/S2 split and unit map (every block, from the counts) and the rows
 //            each 64-token segment gives each unit                   (Brownout Approach, Algorithm 1)
-//   scan     offsets of segments inside units and of units
+//   scan     offsets of segments inside units, unit totals (unit offsets: scanned by the scatter blocks)
 //   scatter  row lists: row_token, row_weight, token_rows (stable: ascending token inside a unit)
 // No floating-point atomics anywhere; integer atomics only where the result does not depend on order.
 #include "internal.h"
@@ -436,29 +436,41 @@ __global__ void __launch_bounds__(256) route_count_kernel(RowArgs p)
         for (int u = lane; u < p.U; u += 64) p.seg_cnt[(size_t)seg * p.U + u] = __popcll(bm[wave][u]);
 }
 
-// One block: per unit, exclusive scan over segments; then exclusive scan over units.
+// One wavefront per unit: exclusive scan of the unit's rows over the segments (lane l owns a contiguous
+// chunk of segments), and the unit's total.
 __global__ void __launch_bounds__(256) route_scan_kernel(RowArgs p)
 {
-    __shared__ int tot[kMaxUnits + 256];
-    __shared__ int wsum[4];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int u = tid; u < p.U; u += 256) {
-        int run = 0;
-        for (int sgm = 0; sgm < p.n_seg; ++sgm) {
-            const int c = p.seg_cnt[(size_t)sgm * p.U + u];
-            p.seg_off[(size_t)sgm * p.U + u] = run;
-            run += c;
-        }
-        tot[u] = run;
-        p.unit_cnt[u] = run;
+    const int lane = threadIdx.x & 63;
+    const int u = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (u >= p.U) return;
+    const int per = (p.n_seg + 63) / 64;
+    const int s_lo = min(p.n_seg, lane * per), s_hi = min(p.n_seg, s_lo + per);
+    int local = 0;
+    for (int sgm = s_lo; sgm < s_hi; ++sgm) local += p.seg_cnt[(size_t)sgm * p.U + u];
+    int incl = local;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_up(incl, off);
+        if (lane >= off) incl += o;
     }
-    __syncthreads();
-    // thread tid owns units [tid*per, tid*per+per)
-    const int per = (p.U + 255) / 256;
+    int run = incl - local;
+    for (int sgm = s_lo; sgm < s_hi; ++sgm) {
+        const int c = p.seg_cnt[(size_t)sgm * p.U + u];
+        p.seg_off[(size_t)sgm * p.U + u] = run;
+        run += c;
+    }
+    if (lane == 63) p.unit_cnt[u] = incl;
+}
+
+// Exclusive scan of unit_cnt into LDS (every block of the scatter needs all unit offsets); off_s[U] = total.
+__device__ __forceinline__ void unit_offsets(const int32_t* unit_cnt, int U, int* off_s, int* wsum, int tid)
+{
+    const int lane = tid & 63, wave = tid >> 6;
+    const int per = (U + 255) / 256;
     int local = 0;
     for (int q = 0; q < per; ++q) {
         const int u = tid * per + q;
-        if (u < p.U) local += tot[u];
+        if (u < U) local += unit_cnt[u];
     }
     int incl = local;
 #pragma unroll
@@ -472,22 +484,27 @@ __global__ void __launch_bounds__(256) route_scan_kernel(RowArgs p)
     for (int w = 0; w < wave; ++w) base += wsum[w];
     for (int q = 0; q < per; ++q) {
         const int u = tid * per + q;
-        if (u < p.U) {
-            p.unit_off[u] = base;
-            base += tot[u];
-            if (u == p.U - 1) {
-                p.unit_off[p.U] = base;
-                if (p.n_rows) p.n_rows[0] = base;
-            }
+        if (u < U) {
+            off_s[u] = base;
+            base += unit_cnt[u];
+            if (u == U - 1) off_s[U] = base;
         }
     }
+    __syncthreads();
 }
 
 __global__ void __launch_bounds__(256) route_scatter_kernel(RowArgs p)
 {
     __shared__ int unit_s[kMaxExperts];
     __shared__ unsigned long long bm[4][kMaxUnits];
+    __shared__ int off_s[kMaxUnits + 1];
+    __shared__ int wsum[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    unit_offsets(p.unit_cnt, p.U, off_s, wsum, tid);
+    if (blockIdx.x == 0) {
+        for (int u = tid; u <= p.U; u += 256) p.unit_off[u] = off_s[u];
+        if (tid == 0 && p.n_rows) p.n_rows[0] = off_s[p.U];
+    }
     if (tid < p.m) unit_s[tid] = p.expert_unit[tid];
     for (int i = tid; i < 4 * kMaxUnits; i += 256) (&bm[0][0])[i] = 0ull;
     __syncthreads();
@@ -510,7 +527,7 @@ __global__ void __launch_bounds__(256) route_scatter_kernel(RowArgs p)
                 for (int q = 0; q < j; ++q)
                     if (unit_s[idx[q]] == u) first = false;
             if (first) {
-                row = p.unit_off[u] + soff[u] + __popcll(bm[wave][u] & below);
+                row = off_s[u] + soff[u] + __popcll(bm[wave][u] & below);
                 float w = wts[j];
                 if (u >= p.m)
                     for (int q = j + 1; q < p.K; ++q)
@@ -523,7 +540,7 @@ __global__ void __launch_bounds__(256) route_scatter_kernel(RowArgs p)
     }
     for (int s = 0; s < p.Ns; ++s) {
         const int u = p.m + p.G + s;
-        const int row = p.unit_off[u] + soff[u] + __popcll(bm[wave][u] & below);
+        const int row = off_s[u] + soff[u] + __popcll(bm[wave][u] & below);
         p.row_token[row] = t;
         p.row_weight[row] = 1.0f;
         p.token_rows[(size_t)t * slots + p.K + s] = row;
@@ -601,7 +618,7 @@ hipError_t launch_route(const Dims& D, const bf16_t* x, const float* gate_w, con
     }
     {
         ProfScope ps(MOE_STAGE_SCAN, s);
-        route_scan_kernel<<<1, 256, 0, s>>>(p);
+        route_scan_kernel<<<ceil_div(D.U, 4), 256, 0, s>>>(p);
     }
     {
         ProfScope ps(MOE_STAGE_SCATTER, s);
