@@ -175,11 +175,13 @@ def cpu_baseline(cfg, L, united, threshold, n_sample):
     r = O.route(x, gw, gb, cfg.K, cfg.way, threshold, False, cfg.score_fn, cfg.n_shared)
     t_route = time.perf_counter() - t0
     per_token_flops = 6.0 * cfg.d * (cfg.F * cfg.K + cfg.F_s * cfg.n_shared)
+    whole = cfg.m * cfg.d * cfg.F <= 6e8        # all experts fit as float arrays: tokens run in parallel
     if n_sample is None:
-        n_sample = int(max(8, min(cfg.T, 1e12 / per_token_flops)))        # ~1 TFLOP of plain loops
+        # about 1 TFLOP of plain loops on all cores, or 100 GFLOP when rows run one at a time on one core
+        n_sample = int(max(8, min(cfg.T, (1e12 if whole else 1e11) / per_token_flops)))
     tokens = np.linspace(0, cfg.T - 1, n_sample).astype(np.int32)
     cores = O.num_threads()
-    if cfg.m * cfg.d * cfg.F <= 6e8:
+    if whole:
         ex, un, sh = tuple(f32(a) for a in L.experts), tuple(f32(a) for a in united), \
             None if L.shared is None else tuple(f32(a) for a in L.shared)
         t0 = time.perf_counter()
