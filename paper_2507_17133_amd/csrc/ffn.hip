@@ -19,6 +19,7 @@
 
 #include <algorithm>
 #include <cstdlib>
+#include <type_traits>
 
 namespace bmoe {
 
@@ -386,51 +387,89 @@ __global__ void __launch_bounds__(512) ffn_gemm_pp_kernel(GemmArgs p)
     if (NSTAGE - 2 < nk && NSTAGE > 2) __builtin_amdgcn_s_waitcnt(vmcnt_imm((NSTAGE - 2) * LD_PER_WAVE));
     else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     lds_barrier();                                        // tile 0 is in LDS for everyone
-    if (grp == 1) lds_barrier();
-    for (int kt = 0; kt < nk; ++kt) {
-        const char* St = smem + (kt % NSTAGE) * STAGE;
+    // Loads of a tile are issued between the MFMAs of a compute phase, one per EV MFMAs, so the texture
+    // path sees a steady trickle instead of a burst that would hold the issuing wave (and with it the
+    // barrier the other group waits at).  The buffer of tile kt-1 is free once both groups have read its
+    // last fragments: group 1 (which runs one barrier late) refills it with tile kt+NSTAGE-1 during the last
+    // compute phase of tile kt-1, group 0 during the first compute phase of tile kt.
+    auto issue_one = [&](int kt, int i) {
+        char* dst = smem + (kt % NSTAGE) * STAGE + wave * 1024;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gptr[i] + kt * BK),
+                                         (__attribute__((address_space(3))) void*)(dst + i * NW * 1024), 16, 0, 0);
+    };
+    auto main_loop = [&](auto grp_tag) {
+        constexpr int GRP = decltype(grp_tag)::value;
+        constexpr int NM = 2 * FM * FN;                                   // MFMAs of one compute phase
+        constexpr int EV = NM / LD_PER_WAVE > 0 ? NM / LD_PER_WAVE : 1;
+        static_assert(LD_PER_WAVE <= NM, "one load slot per MFMA at most");
+        for (int kt = 0; kt < nk; ++kt) {
+            const char* St = smem + (kt % NSTAGE) * STAGE;
+            const int lt = GRP == 0 ? kt + NSTAGE - 1 : kt + NSTAGE;      // tile this wave loads during tile kt
+            const bool ld = lt < nk;
 #pragma unroll
-        for (int ph = 0; ph < P; ++ph) {
-            // -- memory phase.  At the first step of tile kt the buffer of tile kt-1 is free (both groups
-            // finished reading it two barriers ago): refill it with tile kt+NSTAGE-1.
-            if (ph == 0 && kt + NSTAGE - 1 < nk) issue_loads(kt + NSTAGE - 1);
-            bf16x8 af[2][FM], bfr[2][FN];
+            for (int ph = 0; ph < P; ++ph) {
+                // -- memory phase: fragments of this step from LDS
+                bf16x8 af[2][FM], bfr[2][FN];
 #pragma unroll
-            for (int kk = 0; kk < 2; ++kk) {
-                const int sw = (((ph * 2 + kk) * 2 + (lane >> 5)) ^ swz) << 4;
+                for (int kk = 0; kk < 2; ++kk) {
+                    const int sw = (((ph * 2 + kk) * 2 + (lane >> 5)) ^ swz) << 4;
 #pragma unroll
-                for (int i = 0; i < FM; ++i) af[kk][i] = *reinterpret_cast<const bf16x8*>(St + a_off + i * 32 * RB + sw);
-#pragma unroll
-                for (int j = 0; j < FN; ++j) bfr[kk][j] = *reinterpret_cast<const bf16x8*>(St + b_off + j * 32 * RB + sw);
-            }
-            // fragments are in registers (lgkmcnt 0); at the last step of tile kt, tile kt+1 must have
-            // landed too: it is read right after the next barrier pair
-            if (ph == P - 1) {
-                if (NSTAGE > 2 && kt + NSTAGE - 1 < nk)
-                    __builtin_amdgcn_s_waitcnt(vmcnt_lgkm0_imm((NSTAGE - 2) * LD_PER_WAVE));
-                else __builtin_amdgcn_s_waitcnt(vmcnt_lgkm0_imm(0));
-            } else {
-                __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0) only
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            lds_barrier();
-            __builtin_amdgcn_sched_barrier(0);
-            // -- compute phase
-            __builtin_amdgcn_s_setprio(1);
-#pragma unroll
-            for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-                for (int i = 0; i < FM; ++i)
+                    for (int i = 0; i < FM; ++i)
+                        af[kk][i] = *reinterpret_cast<const bf16x8*>(St + a_off + i * 32 * RB + sw);
 #pragma unroll
                     for (int j = 0; j < FN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk][j], af[kk][i], acc[i][j], 0, 0, 0);
-            __builtin_amdgcn_s_setprio(0);
-            __builtin_amdgcn_sched_barrier(0);
-            lds_barrier();
-            __builtin_amdgcn_sched_barrier(0);
+                        bfr[kk][j] = *reinterpret_cast<const bf16x8*>(St + b_off + j * 32 * RB + sw);
+                }
+                // fragments are in registers (lgkmcnt 0).  Group 1's last memory phase of tile kt is the last
+                // thing before group 0 reads tile kt+1: its loads of that tile must have landed.
+                if (GRP == 1 && ph == P - 1) {
+                    if (NSTAGE > 2 && kt + NSTAGE - 1 < nk)
+                        __builtin_amdgcn_s_waitcnt(vmcnt_lgkm0_imm((NSTAGE - 2) * LD_PER_WAVE));
+                    else __builtin_amdgcn_s_waitcnt(vmcnt_lgkm0_imm(0));
+                } else {
+                    __builtin_amdgcn_s_waitcnt(0xC07F);   // lgkmcnt(0) only
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                lds_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+                // -- compute phase
+                const bool load_phase = GRP == 0 ? ph == 0 : ph == P - 1;
+                __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+                for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+                    for (int i = 0; i < FM; ++i)
+#pragma unroll
+                        for (int j = 0; j < FN; ++j) {
+                            acc[i][j] =
+                                __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk][j], af[kk][i], acc[i][j], 0, 0, 0);
+                            const int mi = (kk * FM + i) * FN + j;
+                            if (load_phase && mi % EV == 0 && mi / EV < LD_PER_WAVE) {
+                                __builtin_amdgcn_sched_barrier(0);
+                                if (ld) issue_one(lt, mi / EV);
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                        }
+                __builtin_amdgcn_s_setprio(0);
+                // group 0's last compute phase of tile kt ends right before it reads tile kt+1
+                if (GRP == 0 && ph == P - 1) {
+                    if (NSTAGE > 2 && kt + NSTAGE - 1 < nk) __builtin_amdgcn_s_waitcnt(vmcnt_imm((NSTAGE - 2) * LD_PER_WAVE));
+                    else __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                lds_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
+    };
+    if (grp == 0) {
+        main_loop(std::integral_constant<int, 0>{});
+        lds_barrier();
+    } else {
+        if (NSTAGE - 1 < nk) issue_loads(NSTAGE - 1);     // its "compute phase before tile 0"
+        lds_barrier();
+        main_loop(std::integral_constant<int, 1>{});
     }
-    if (grp == 0) lds_barrier();
     store_tile<FM, FN, TM, TN, SWIGLU>(p, t, acc, wm, wn, lane);
 }
 
