@@ -474,6 +474,140 @@ __global__ void __launch_bounds__(512) ffn_gemm_pp_kernel(GemmArgs p)
 }
 
 // ------------------------------------------------------------------------------------------------
+// Register-staged large-tile kernel (BM x 256 x 64, 8 waves as 2 x 4, same ping-pong as above) with a
+// three-deep pipeline out of two LDS buffers: while tile kt is multiplied out of one buffer, tile kt+1
+// sits in registers (it was requested during tile kt-1) and is written to the other buffer in this tile's
+// memory phases, and tile kt+2 is requested between the MFMAs of the compute phases.  A load has a full
+// tile time to return, and only plain vector loads and LDS stores are used in the loop.  Past the end
+// of K the loads are clamped to the last tile (their data is never read).
+// ------------------------------------------------------------------------------------------------
+// The compiler's own wait insertion would drain every load before the first LDS store of a tile, so the
+// staging loads are opaque to it and waited for by hand (s_waitcnt vmcnt) before their registers are read.
+__device__ __forceinline__ void load_stage(u32x4& dst, const bf16_t* src)
+{
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(src));
+}
+
+template <int BM, bool SWIGLU>
+__global__ void __launch_bounds__(512) ffn_gemm_rs_kernel(GemmArgs p)
+{
+    constexpr int BK = 64, BN = 256, WN = 4, NW = 8, P = 2;
+    using L = Lds<BK>;
+    constexpr int TM = BM / 2, TN = BN / WN, FM = TM / 32, FN = TN / 32;
+    constexpr int RB = L::RB, RPG = L::RPG;
+    constexpr int STAGE = (BM + BN) * RB;
+    constexpr int GROUPS = (BM + BN) / RPG;
+    constexpr int LD_PER_WAVE = GROUPS / NW;
+    constexpr int LP = LD_PER_WAVE / P;                  // loads (and LDS stores) per phase
+    constexpr int NM = 2 * FM * FN;                      // MFMAs per compute phase
+    constexpr int EV = NM / LP;
+    static_assert(GROUPS % NW == 0 && LD_PER_WAVE % P == 0 && EV >= 1, "loader shape");
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    Tile t;
+    if (!decode_tile<SWIGLU ? BN / 2 : BN, SWIGLU>(p, t)) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 2, wn = wave & 3;
+    const int grp = wm;
+    int k_first, nk;
+    k_range<BK>(p, t, k_first, nk);
+
+    const bf16_t* gptr[LD_PER_WAVE];
+#pragma unroll
+    for (int i = 0; i < LD_PER_WAVE; ++i) {
+        const int row = (wave + i * NW) * RPG + L::lane_row(lane);
+        const bf16_t* base = row < BM ? a_row_ptr(p, t, row) : b_row_ptr<TN, SWIGLU>(p, t, row - BM);
+        gptr[i] = base + L::lane_chunk(lane, row) * 8 + (size_t)k_first * BK;
+    }
+    f32x16 acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+    if (nk <= 0) {
+        store_tile<FM, FN, TM, TN, SWIGLU>(p, t, acc, wm, wn, lane);
+        return;
+    }
+    const int last = nk - 1;
+    // tile 0 straight into buffer 0, tile 1 into registers
+    {
+        char* dst = smem + wave * 1024;
+#pragma unroll
+        for (int i = 0; i < LD_PER_WAVE; ++i)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gptr[i],
+                                             (__attribute__((address_space(3))) void*)(dst + i * NW * 1024), 16, 0, 0);
+    }
+    u32x4 stg[LD_PER_WAVE];
+#pragma unroll
+    for (int i = 0; i < LD_PER_WAVE; ++i) load_stage(stg[i], gptr[i] + min(1, last) * BK);
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(LD_PER_WAVE));   // the LDS loads are the older ones
+    const int a_off = (wm * TM + (lane & 31)) * RB;
+    const int b_off = BM * RB + (wn * TN + (lane & 31)) * RB;
+    const int w_off = wave * 1024 + lane * 16;
+    const int swz = L::read_swz(lane);
+    lds_barrier();                                        // tile 0 is in LDS for everyone
+    if (grp == 1) lds_barrier();
+    for (int kt = 0; kt < nk; ++kt) {
+        const char* St = smem + (kt & 1) * STAGE;
+        char* Wn = smem + ((kt + 1) & 1) * STAGE + w_off;  // buffer of tile kt-1: both groups have left it
+        const long knext = (long)min(kt + 2, last) * BK;
+#pragma unroll
+        for (int ph = 0; ph < P; ++ph) {
+            // -- memory phase: this step's fragments out of LDS, then this phase's share of tile kt+1 into LDS
+            bf16x8 af[2][FM], bfr[2][FN];
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk) {
+                const int sw = (((ph * 2 + kk) * 2 + (lane >> 5)) ^ swz) << 4;
+#pragma unroll
+                for (int i = 0; i < FM; ++i) af[kk][i] = *reinterpret_cast<const bf16x8*>(St + a_off + i * 32 * RB + sw);
+#pragma unroll
+                for (int j = 0; j < FN; ++j) bfr[kk][j] = *reinterpret_cast<const bf16x8*>(St + b_off + j * 32 * RB + sw);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            // in flight: this phase's LP registers (requested a tile ago) and the LP requested one compute
+            // phase ago; loads return in order
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(LP));
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int q = 0; q < LP; ++q)
+                *reinterpret_cast<u32x4*>(Wn + (ph * LP + q) * NW * 1024) = stg[ph * LP + q];
+            __builtin_amdgcn_s_waitcnt(0xC07F);           // lgkmcnt(0): fragments here, stores done
+            __builtin_amdgcn_sched_barrier(0);
+            lds_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+            // -- compute phase, with this phase's share of tile kt+2 requested between the MFMAs
+            __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+                for (int i = 0; i < FM; ++i)
+#pragma unroll
+                    for (int j = 0; j < FN; ++j) {
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk][j], af[kk][i], acc[i][j], 0, 0, 0);
+                        const int mi = (kk * FM + i) * FN + j;
+                        if (mi % EV == 0 && mi / EV < LP) {
+                            __builtin_amdgcn_sched_barrier(0);
+                            const int li = ph * LP + mi / EV;
+                            load_stage(stg[li], gptr[li] + knext);
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                    }
+            __builtin_amdgcn_s_setprio(0);
+            __builtin_amdgcn_sched_barrier(0);
+            lds_barrier();
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    if (grp == 0) lds_barrier();
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));             // the clamped tail loads still target stg
+#pragma unroll
+    for (int i = 0; i < LD_PER_WAVE; ++i) asm volatile("" ::"v"(stg[i]));
+    store_tile<FM, FN, TM, TN, SWIGLU>(p, t, acc, wm, wn, lane);
+}
+
+// ------------------------------------------------------------------------------------------------
 // combine: one thread = 8 columns of one token; rows summed in slot order, shared experts first.
 // ------------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) combine_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ Y,
@@ -551,11 +685,21 @@ static hipError_t launch_pp(const GemmArgs& a, int max_mtiles, hipStream_t s)
                         s);
 }
 
+template <int BM, bool SWIGLU>
+static hipError_t launch_rs(const GemmArgs& a, int max_mtiles, hipStream_t s)
+{
+    constexpr int LDS = 2 * (BM + 256) * 64 * 2;
+    static bool attr_set = false;
+    return launch_tiles(ffn_gemm_rs_kernel<BM, SWIGLU>, attr_set, 512, LDS, SWIGLU ? 128 : 256, a, max_mtiles, s);
+}
+
 template <bool SWIGLU>
 static hipError_t dispatch_gemm(int BM, const GemmArgs& a, int max_mtiles, hipStream_t s)
 {
     switch (BM) {
-        case 256: return launch_pp<256, 64, 2, SWIGLU>(a, max_mtiles, s);
+        case 256:
+            if (std::getenv("BROWNOUT_MOE_PP")) return launch_pp<256, 64, 2, SWIGLU>(a, max_mtiles, s);
+            return launch_rs<256, SWIGLU>(a, max_mtiles, s);
         case 128: return launch_pp<128, 64, 3, SWIGLU>(a, max_mtiles, s);
         case 64: return launch_small<64, 256, 1, 4, 64, 3, SWIGLU>(a, max_mtiles, s);
         default: return launch_small<32, 256, 1, 4, 64, 4, SWIGLU>(a, max_mtiles, s);
