@@ -25,6 +25,7 @@ namespace bmoe {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ unsigned short f2bf(float f)
@@ -153,16 +154,16 @@ __device__ __forceinline__ const bf16_t* a_row_ptr(const GemmArgs& p, const Tile
     return p.A + src_row * p.lda;
 }
 
-// Weight row behind row n of the block's B tile.  GEMM1: the wave tile's 32-column MFMA tiles alternate
-// W1 / W3 of the same 32 f columns.  Columns past N are clamped (never stored).
-template <int TN, bool SWIGLU>
+// Weight row behind row n of the block's B tile.  GEMM1: the wave tile's TW-column MFMA tiles alternate
+// W1 / W3 of the same TW f columns.  Columns past N are clamped (never stored).
+template <int TN, bool SWIGLU, int TW = 32>
 __device__ __forceinline__ const bf16_t* b_row_ptr(const GemmArgs& p, const Tile& t, int n)
 {
     int col;
     const bf16_t* W = t.Wa;
     if (SWIGLU) {
-        const int w_n = n / TN, j = (n % TN) >> 5, c = n & 31;
-        col = t.n0 + (w_n * (TN / 64) + (j >> 1)) * 32 + c;
+        const int w_n = n / TN, j = (n % TN) / TW, c = n % TW;
+        col = t.n0 + (w_n * (TN / (2 * TW)) + (j >> 1)) * TW + c;
         if (j & 1) W = t.Wb;
     } else {
         col = t.n0 + n;
@@ -214,6 +215,48 @@ __device__ __forceinline__ void store_tile(const GemmArgs& p, const Tile& t, con
                         *reinterpret_cast<uint2*>(orow + col) =
                             make_uint2((unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16));
                 }
+            }
+        }
+    }
+}
+
+// Epilogue for 16x16 MFMA tiles (same transposed product): a lane holds, for output row lane&15, the four
+// consecutive columns 4*(lane>>4) + 0..3 of each 16x16 tile.
+template <int FM, int FN, int TM, int TN, bool SWIGLU>
+__device__ __forceinline__ void store_tile16(const GemmArgs& p, const Tile& t, const f32x4 (&acc)[FM][FN], int wm,
+                                             int wn, int lane)
+{
+    unsigned short* out = reinterpret_cast<unsigned short*>(p.out) + (size_t)t.kslice * p.plane;
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+        const int rl = wm * TM + i * 16 + (lane & 15);
+        if (rl >= t.nrows) continue;
+        unsigned short* orow = out + (long)(t.row0 + rl) * p.ldo;
+        if (SWIGLU) {
+#pragma unroll
+            for (int jp = 0; jp < FN / 2; ++jp) {
+                const int col = t.n0 + (wn * (TN / 32) + jp) * 16 + 4 * (lane >> 4);
+                unsigned short h[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float g = acc[i][2 * jp][e], u = acc[i][2 * jp + 1][e];
+                    h[e] = f2bf(g * __frcp_rn(1.0f + __expf(-g)) * u);
+                }
+                if (col < p.N)
+                    *reinterpret_cast<uint2*>(orow + col) =
+                        make_uint2((unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16));
+            }
+        } else {
+            const float w = p.row_weight[t.row0 + rl];
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                const int col = t.n0 + wn * TN + j * 16 + 4 * (lane >> 4);
+                unsigned short h[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) h[e] = f2bf(acc[i][j][e] * w);
+                if (col < p.N)
+                    *reinterpret_cast<uint2*>(orow + col) =
+                        make_uint2((unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16));
             }
         }
     }
@@ -493,13 +536,13 @@ __global__ void __launch_bounds__(512) ffn_gemm_rs_kernel(GemmArgs p)
 {
     constexpr int BK = 64, BN = 256, WN = 4, NW = 8, P = 2;
     using L = Lds<BK>;
-    constexpr int TM = BM / 2, TN = BN / WN, FM = TM / 32, FN = TN / 32;
+    constexpr int TM = BM / 2, TN = BN / WN, FM = TM / 16, FN = TN / 16;
     constexpr int RB = L::RB, RPG = L::RPG;
     constexpr int STAGE = (BM + BN) * RB;
     constexpr int GROUPS = (BM + BN) / RPG;
     constexpr int LD_PER_WAVE = GROUPS / NW;
     constexpr int LP = LD_PER_WAVE / P;                  // loads (and LDS stores) per phase
-    constexpr int NM = 2 * FM * FN;                      // MFMAs per compute phase
+    constexpr int NM = FM * FN;                          // MFMAs (16x16x32) per compute phase
     constexpr int EV = NM / LP;
     static_assert(GROUPS % NW == 0 && LD_PER_WAVE % P == 0 && EV >= 1, "loader shape");
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -516,18 +559,18 @@ __global__ void __launch_bounds__(512) ffn_gemm_rs_kernel(GemmArgs p)
 #pragma unroll
     for (int i = 0; i < LD_PER_WAVE; ++i) {
         const int row = (wave + i * NW) * RPG + L::lane_row(lane);
-        const bf16_t* base = row < BM ? a_row_ptr(p, t, row) : b_row_ptr<TN, SWIGLU>(p, t, row - BM);
+        const bf16_t* base = row < BM ? a_row_ptr(p, t, row) : b_row_ptr<TN, SWIGLU, 16>(p, t, row - BM);
         gptr[i] = base + L::lane_chunk(lane, row) * 8 + (size_t)k_first * BK;
     }
-    f32x16 acc[FM][FN];
+    f32x4 acc[FM][FN];
 #pragma unroll
     for (int i = 0; i < FM; ++i)
 #pragma unroll
         for (int j = 0; j < FN; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+            for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.0f;
     if (nk <= 0) {
-        store_tile<FM, FN, TM, TN, SWIGLU>(p, t, acc, wm, wn, lane);
+        store_tile16<FM, FN, TM, TN, SWIGLU>(p, t, acc, wm, wn, lane);
         return;
     }
     const int last = nk - 1;
@@ -543,10 +586,10 @@ __global__ void __launch_bounds__(512) ffn_gemm_rs_kernel(GemmArgs p)
 #pragma unroll
     for (int i = 0; i < LD_PER_WAVE; ++i) load_stage(stg[i], gptr[i] + min(1, last) * BK);
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(LD_PER_WAVE));   // the LDS loads are the older ones
-    const int a_off = (wm * TM + (lane & 31)) * RB;
-    const int b_off = BM * RB + (wn * TN + (lane & 31)) * RB;
+    const int a_off = (wm * TM + (lane & 15)) * RB;
+    const int b_off = BM * RB + (wn * TN + (lane & 15)) * RB;
     const int w_off = wave * 1024 + lane * 16;
-    const int swz = L::read_swz(lane);
+    const int swz = ((lane & 15) / L::WR) & (L::CPR - 1);
     lds_barrier();                                        // tile 0 is in LDS for everyone
     if (grp == 1) lds_barrier();
     for (int kt = 0; kt < nk; ++kt) {
@@ -556,14 +599,13 @@ __global__ void __launch_bounds__(512) ffn_gemm_rs_kernel(GemmArgs p)
 #pragma unroll
         for (int ph = 0; ph < P; ++ph) {
             // -- memory phase: this step's fragments out of LDS, then this phase's share of tile kt+1 into LDS
-            bf16x8 af[2][FM], bfr[2][FN];
+            bf16x8 af[FM], bfr[FN];
+            {
+                const int sw = ((ph * 4 + (lane >> 4)) ^ swz) << 4;
 #pragma unroll
-            for (int kk = 0; kk < 2; ++kk) {
-                const int sw = (((ph * 2 + kk) * 2 + (lane >> 5)) ^ swz) << 4;
+                for (int i = 0; i < FM; ++i) af[i] = *reinterpret_cast<const bf16x8*>(St + a_off + i * 16 * RB + sw);
 #pragma unroll
-                for (int i = 0; i < FM; ++i) af[kk][i] = *reinterpret_cast<const bf16x8*>(St + a_off + i * 32 * RB + sw);
-#pragma unroll
-                for (int j = 0; j < FN; ++j) bfr[kk][j] = *reinterpret_cast<const bf16x8*>(St + b_off + j * 32 * RB + sw);
+                for (int j = 0; j < FN; ++j) bfr[j] = *reinterpret_cast<const bf16x8*>(St + b_off + j * 16 * RB + sw);
             }
             __builtin_amdgcn_sched_barrier(0);
             // in flight: this phase's LP registers (requested a tile ago) and the LP requested one compute
@@ -580,20 +622,18 @@ __global__ void __launch_bounds__(512) ffn_gemm_rs_kernel(GemmArgs p)
             // -- compute phase, with this phase's share of tile kt+2 requested between the MFMAs
             __builtin_amdgcn_s_setprio(1);
 #pragma unroll
-            for (int kk = 0; kk < 2; ++kk)
+            for (int i = 0; i < FM; ++i)
 #pragma unroll
-                for (int i = 0; i < FM; ++i)
-#pragma unroll
-                    for (int j = 0; j < FN; ++j) {
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk][j], af[kk][i], acc[i][j], 0, 0, 0);
-                        const int mi = (kk * FM + i) * FN + j;
-                        if (mi % EV == 0 && mi / EV < LP) {
-                            __builtin_amdgcn_sched_barrier(0);
-                            const int li = ph * LP + mi / EV;
-                            load_stage(stg[li], gptr[li] + knext);
-                            __builtin_amdgcn_sched_barrier(0);
-                        }
+                for (int j = 0; j < FN; ++j) {
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
+                    const int mi = i * FN + j;
+                    if (mi % EV == 0 && mi / EV < LP) {
+                        __builtin_amdgcn_sched_barrier(0);
+                        const int li = ph * LP + mi / EV;
+                        load_stage(stg[li], gptr[li] + knext);
+                        __builtin_amdgcn_sched_barrier(0);
                     }
+                }
             __builtin_amdgcn_s_setprio(0);
             __builtin_amdgcn_sched_barrier(0);
             lds_barrier();
@@ -604,6 +644,144 @@ __global__ void __launch_bounds__(512) ffn_gemm_rs_kernel(GemmArgs p)
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));             // the clamped tail loads still target stg
 #pragma unroll
     for (int i = 0; i < LD_PER_WAVE; ++i) asm volatile("" ::"v"(stg[i]));
+    store_tile16<FM, FN, TM, TN, SWIGLU>(p, t, acc, wm, wn, lane);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Ring kernel (BM x 256, 8 waves as 2 x 4, same ping-pong): k tiles of 64 are requested as whole 128-byte
+// lines by direct global->LDS loads, but live in LDS as two half-tiles of 32 k (64-byte rows) that are
+// consumed, and freed, one per step.  Five half-tile slots form a ring, so the two halves of tile kt+2
+// can be requested while tile kt is multiplied and tile kt+1 is landing: a request has at least a full
+// tile time to return although only 2.5 tiles fit in LDS.  The two loads of one row group (first and
+// second half of the same lines) are issued back to back.  Group 1 issues its loads in the first compute
+// phase of a tile, group 0 in the second; past the end of K loads are clamped to the last tile and land
+// in slots nobody reads any more.
+// ------------------------------------------------------------------------------------------------
+template <int BM, bool SWIGLU>
+__global__ void __launch_bounds__(512) ffn_gemm_ring_kernel(GemmArgs p)
+{
+    constexpr int BN = 256, WN = 4, NW = 8, HK = 32, RING = 5;
+    using L = Lds<HK>;
+    constexpr int TM = BM / 2, TN = BN / WN, FM = TM / 32, FN = TN / 32;
+    constexpr int RB = L::RB, RPG = L::RPG;
+    constexpr int STAGE = (BM + BN) * RB;
+    constexpr int GROUPS = (BM + BN) / RPG;
+    constexpr int GPW = GROUPS / NW;                     // row groups per wave; two loads each per tile
+    constexpr int NLD = 2 * GPW;
+    constexpr int NM = 2 * FM * FN;
+    constexpr int EV = NM / NLD > 0 ? NM / NLD : 1;
+    static_assert(GROUPS % NW == 0 && NLD <= NM, "loader shape");
+    static_assert(RING * STAGE <= 160 * 1024, "LDS budget of one CU");
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    Tile t;
+    if (!decode_tile<SWIGLU ? BN / 2 : BN, SWIGLU>(p, t)) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+    const int wm = wave >> 2, wn = wave & 3;
+    const int grp = wm;
+    int k_first, nk64;
+    k_range<64>(p, t, k_first, nk64);
+
+    const bf16_t* gptr[GPW];
+#pragma unroll
+    for (int i = 0; i < GPW; ++i) {
+        const int row = (wave + i * NW) * RPG + L::lane_row(lane);
+        const bf16_t* base = row < BM ? a_row_ptr(p, t, row) : b_row_ptr<TN, SWIGLU>(p, t, row - BM);
+        gptr[i] = base + L::lane_chunk(lane, row) * 8 + (size_t)k_first * 64;
+    }
+    f32x16 acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+    if (nk64 <= 0) {
+        store_tile<FM, FN, TM, TN, SWIGLU>(p, t, acc, wm, wn, lane);
+        return;
+    }
+    const int nk = nk64, last = nk - 1;
+    // load j of tile kt: row group j/2, k half j%2, into ring slot s0 (first half) or s1 (second half)
+    auto issue = [&](int kt, int s0, int s1, int j) {
+        const int i = j >> 1, half = j & 1;
+        char* dst = smem + (half ? s1 : s0) * STAGE + (wave_s + i * NW) * 1024;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gptr[i] + (long)kt * 64 + half * HK),
+                                         (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+    };
+#pragma unroll
+    for (int j = 0; j < NLD; ++j) issue(0, 0, 1, j);
+#pragma unroll
+    for (int j = 0; j < NLD; ++j) issue(min(1, last), 2, 3, j);
+    const int a_off = (wm * TM + (lane & 31)) * RB;
+    const int b_off = BM * RB + (wn * TN + (lane & 31)) * RB;
+    const int swz = L::read_swz(lane);
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(NLD));
+    lds_barrier();                                        // tile 0 is in LDS for everyone
+
+    auto main_loop = [&](auto grp_tag) {
+        constexpr int GRP = decltype(grp_tag)::value;
+        int r0 = 0;                                       // ring slot of the first half of tile kt
+        for (int kt = 0; kt < nk; ++kt) {
+            const int r1 = r0 + 1 == RING ? 0 : r0 + 1;
+            const int l0 = r0 + 4 >= RING ? r0 + 4 - RING : r0 + 4, l1 = r0;   // slots of tile kt+2's halves
+            const int lt = min(kt + 2, last);
+#pragma unroll
+            for (int ph = 0; ph < 2; ++ph) {
+                const char* St = smem + (ph == 0 ? r0 : r1) * STAGE;
+                bf16x8 af[2][FM], bfr[2][FN];
+#pragma unroll
+                for (int kk = 0; kk < 2; ++kk) {
+                    const int sw = ((kk * 2 + (lane >> 5)) ^ swz) << 4;
+#pragma unroll
+                    for (int i = 0; i < FM; ++i)
+                        af[kk][i] = *reinterpret_cast<const bf16x8*>(St + a_off + i * 32 * RB + sw);
+#pragma unroll
+                    for (int j = 0; j < FN; ++j)
+                        bfr[kk][j] = *reinterpret_cast<const bf16x8*>(St + b_off + j * 32 * RB + sw);
+                }
+                // group 1's last memory phase of tile kt is the last thing before group 0 reads tile kt+1:
+                // its loads of that tile (all but the youngest NLD) must have landed
+                if (GRP == 1 && ph == 1) __builtin_amdgcn_s_waitcnt(vmcnt_lgkm0_imm(NLD));
+                else __builtin_amdgcn_s_waitcnt(0xC07F);
+                __builtin_amdgcn_sched_barrier(0);
+                lds_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+                const bool load_phase = GRP == 0 ? ph == 1 : ph == 0;
+                __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+                for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+                    for (int i = 0; i < FM; ++i)
+#pragma unroll
+                        for (int j = 0; j < FN; ++j) {
+                            acc[i][j] =
+                                __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk][j], af[kk][i], acc[i][j], 0, 0, 0);
+                            const int mi = (kk * FM + i) * FN + j;
+                            if (load_phase && mi % EV == 0 && mi / EV < NLD) {
+                                __builtin_amdgcn_sched_barrier(0);
+                                issue(lt, l0, l1, mi / EV);
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                        }
+                __builtin_amdgcn_s_setprio(0);
+                // group 0 ends tile kt right before it reads tile kt+1
+                if (GRP == 0 && ph == 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm(NLD));
+                __builtin_amdgcn_sched_barrier(0);
+                lds_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            r0 = r0 + 2 >= RING ? r0 + 2 - RING : r0 + 2;
+        }
+    };
+    if (grp == 0) {
+        main_loop(std::integral_constant<int, 0>{});
+        lds_barrier();
+    } else {
+        lds_barrier();
+        main_loop(std::integral_constant<int, 1>{});
+    }
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));             // clamped tail loads still target this block's LDS
     store_tile<FM, FN, TM, TN, SWIGLU>(p, t, acc, wm, wn, lane);
 }
 
@@ -693,12 +871,21 @@ static hipError_t launch_rs(const GemmArgs& a, int max_mtiles, hipStream_t s)
     return launch_tiles(ffn_gemm_rs_kernel<BM, SWIGLU>, attr_set, 512, LDS, SWIGLU ? 128 : 256, a, max_mtiles, s);
 }
 
+template <int BM, bool SWIGLU>
+static hipError_t launch_ring(const GemmArgs& a, int max_mtiles, hipStream_t s)
+{
+    constexpr int LDS = 5 * (BM + 256) * 32 * 2;
+    static bool attr_set = false;
+    return launch_tiles(ffn_gemm_ring_kernel<BM, SWIGLU>, attr_set, 512, LDS, SWIGLU ? 128 : 256, a, max_mtiles, s);
+}
+
 template <bool SWIGLU>
 static hipError_t dispatch_gemm(int BM, const GemmArgs& a, int max_mtiles, hipStream_t s)
 {
     switch (BM) {
         case 256:
             if (std::getenv("BROWNOUT_MOE_PP")) return launch_pp<256, 64, 2, SWIGLU>(a, max_mtiles, s);
+            if (std::getenv("BROWNOUT_MOE_RING")) return launch_ring<256, SWIGLU>(a, max_mtiles, s);
             return launch_rs<256, SWIGLU>(a, max_mtiles, s);
         case 128: return launch_pp<128, 64, 3, SWIGLU>(a, max_mtiles, s);
         case 64: return launch_small<64, 256, 1, 4, 64, 3, SWIGLU>(a, max_mtiles, s);
