@@ -531,6 +531,21 @@ __device__ __forceinline__ void load_stage(u32x4& dst, const bf16_t* src)
     asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(src));
 }
 
+// Tells the compiler that a pointer is the same in every lane (keeps it in scalar registers).
+__device__ __forceinline__ const bf16_t* uniform_ptr(const bf16_t* ptr)
+{
+    const unsigned long long v = reinterpret_cast<unsigned long long>(ptr);
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
+    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+    return reinterpret_cast<const bf16_t*>(((unsigned long long)hi << 32) | lo);
+}
+
+// Same with a wave-uniform base address in scalar registers and a 32-bit byte offset per lane.
+__device__ __forceinline__ void load_stage_s(u32x4& dst, const bf16_t* base, unsigned off)
+{
+    asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst) : "v"(off), "s"(base));
+}
+
 template <int BM, bool SWIGLU>
 __global__ void __launch_bounds__(512) ffn_gemm_rs_kernel(GemmArgs p)
 {
@@ -644,6 +659,183 @@ __global__ void __launch_bounds__(512) ffn_gemm_rs_kernel(GemmArgs p)
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));             // the clamped tail loads still target stg
 #pragma unroll
     for (int i = 0; i < LD_PER_WAVE; ++i) asm volatile("" ::"v"(stg[i]));
+    store_tile16<FM, FN, TM, TN, SWIGLU>(p, t, acc, wm, wn, lane);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Four-wave kernel (256 x 256 x 64 block tile, one wave per SIMD, wave tile 128 x 128, 16x16x32 MFMA,
+// accumulators in the accumulation registers).  One instruction stream per SIMD feeds the matrix pipe
+// without hand-offs: a k tile is two steps of 64 MFMAs, and between the MFMAs of a step the wave reads
+// the next step's fragments from LDS (double-buffered in registers) and issues direct global->LDS loads.
+// The 160 KiB of LDS hold two buffers for the A rows (activations, mostly L2 hits) and three for the B
+// rows (weights, which stream from memory and need the longer lead).  One barrier per k tile, three
+// quarters into its first step, when a wave has read its last fragments of tile kt and its loads of tile
+// kt+1 have landed; right after it the A rows of tile kt+2 are requested into the buffer just left, and
+// in the second step the B rows of tile kt+3.  Requests past the end of K are clamped to the last tile
+// (never read).
+// ------------------------------------------------------------------------------------------------
+template <bool SWIGLU>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) ffn_gemm_w4_kernel(GemmArgs p)
+{
+    constexpr int BM = 256, BN = 256, BK = 64, NW = 4;
+    using L = Lds<BK>;
+    constexpr int TM = 128, TN = 128, FM = TM / 16, FN = TN / 16;
+    constexpr int RB = L::RB, RPG = L::RPG;
+    constexpr int ABUF = BM * RB, BBUF = BN * RB;        // 32 KiB each
+    constexpr int B_BASE = 2 * ABUF;
+    constexpr int HL = BM / RPG / NW;                    // 8 loads of A rows and 8 of B rows per wave and tile
+    static_assert(2 * ABUF + 3 * BBUF <= 160 * 1024, "LDS budget of one CU");
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    Tile t;
+    if (!decode_tile<SWIGLU ? BN / 2 : BN, SWIGLU>(p, t)) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    int k_first, nk;
+    k_range<BK>(p, t, k_first, nk);
+
+    // Load i of a wave covers rows (wave + 4 i) * 8 .. + 8 of the A (or B) tile.  An address is a
+    // wave-uniform base (scalar registers) plus a 32-bit lane offset: A rows are gathered, so each load has
+    // its own lane offset from the start of A; the B rows of a load are 8 consecutive weight rows, so all
+    // B loads share one lane offset.  The swizzle term ((row/2)&7) is the same for every load of a lane
+    // because (wave + 4 i) * 4 == 4 * (wave & 1) (mod 8).
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+    const int r8 = lane >> 3;
+    const int csw = (lane & 7) ^ ((((wave & 1) << 2) + (r8 >> 1)) & 7);
+    unsigned offA[HL];
+#pragma unroll
+    for (int i = 0; i < HL; ++i) {
+        const int row = (wave + i * NW) * RPG + r8;
+        const int r = row < t.nrows ? row : 0;
+        const long src_row = p.gather ? (long)p.gather[t.row0 + r] : (long)(t.row0 + r);
+        offA[i] = (unsigned)(src_row * p.lda * 2 + csw * 16);
+    }
+    const unsigned offB = (unsigned)((long)r8 * p.K * 2 + csw * 16);
+    const bf16_t* baseA = uniform_ptr(p.A + (size_t)k_first * BK);
+    const bf16_t* baseB[HL];
+#pragma unroll
+    for (int q = 0; q < HL; ++q) {
+        const int g = wave_s + NW * q;                    // 8-row group inside the B tile, 0..31
+        const bf16_t* W = t.Wa;
+        int col0;
+        if (SWIGLU) {
+            const int w_n = g >> 4, j16 = (g & 15) >> 1;
+            col0 = t.n0 + (w_n * 4 + (j16 >> 1)) * 16 + (g & 1) * 8;
+            if (j16 & 1) W = t.Wb;
+        } else {
+            col0 = t.n0 + g * 8;
+        }
+        col0 = min(col0, p.N - 8);                        // columns past N are never stored
+        baseB[q] = uniform_ptr(W + (size_t)col0 * p.K + (size_t)k_first * BK);
+    }
+    // one direct load: 8 rows x 128 bytes into 1 KiB of LDS
+    auto load_a = [&](int i, int tile, int abuf) {
+        const char* src = reinterpret_cast<const char*>(baseA + (long)tile * BK) + offA[i];
+        char* dst = smem + abuf * ABUF + (wave_s + i * NW) * 1024;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                         (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+    };
+    auto load_b = [&](int q, int tile, int bbuf) {
+        const char* src = reinterpret_cast<const char*>(baseB[q] + (long)tile * BK) + offB;
+        char* dst = smem + B_BASE + bbuf * BBUF + (wave_s + q * NW) * 1024;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                         (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+    };
+
+    f32x4 acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.0f;
+    if (nk <= 0) {
+        store_tile16<FM, FN, TM, TN, SWIGLU>(p, t, acc, wm, wn, lane);
+        return;
+    }
+    const int last = nk - 1;
+    // prologue: tiles 0 and 1, and the B rows of tile 2
+#pragma unroll
+    for (int i = 0; i < HL; ++i) load_a(i, 0, 0);
+#pragma unroll
+    for (int q = 0; q < HL; ++q) load_b(q, 0, 0);
+#pragma unroll
+    for (int i = 0; i < HL; ++i) load_a(i, min(1, last), 1);
+#pragma unroll
+    for (int q = 0; q < HL; ++q) load_b(q, min(1, last), 1);
+#pragma unroll
+    for (int q = 0; q < HL; ++q) load_b(q, min(2, last), 2);
+    const int a_off = (wm * TM + (lane & 15)) * RB;
+    const int b_off = B_BASE + (wn * TN + (lane & 15)) * RB;
+    const int swz = ((lane & 15) / L::WR) & (L::CPR - 1);
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(3 * HL));        // tile 0 has landed
+    lds_barrier();
+
+    bf16x8 fa[2][FM], fb[2][FN];
+    auto read_frag_a = [&](int abuf, int half, int i, int buf) {
+        const int sw = ((half * 4 + (lane >> 4)) ^ swz) << 4;
+        fa[buf][i] = *reinterpret_cast<const bf16x8*>(smem + abuf * ABUF + a_off + i * 16 * RB + sw);
+    };
+    auto read_frag_b = [&](int bbuf, int half, int j, int buf) {
+        const int sw = ((half * 4 + (lane >> 4)) ^ swz) << 4;
+        fb[buf][j] = *reinterpret_cast<const bf16x8*>(smem + bbuf * BBUF + b_off + j * 16 * RB + sw);
+    };
+#pragma unroll
+    for (int i = 0; i < FM; ++i) read_frag_a(0, 0, i, 0);
+#pragma unroll
+    for (int j = 0; j < FN; ++j) read_frag_b(0, 0, j, 0);
+    __builtin_amdgcn_s_waitcnt(0xC07F);
+
+    int b_cur = 0;                                        // B buffer of tile kt (kt mod 3)
+    for (int kt = 0; kt < nk; ++kt) {
+        const int a_cur = kt & 1;
+        const int b_nxt = b_cur == 2 ? 0 : b_cur + 1;
+        const int t2 = min(kt + 2, last), t3 = min(kt + 3, last);
+#pragma unroll
+        for (int st = 0; st < 2; ++st) {
+            // fragments of the next step: second half of this tile, or first half of the next tile
+            const int a_rd = st == 0 ? a_cur : a_cur ^ 1;
+            const int b_rd = st == 0 ? b_cur : b_nxt;
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j) {
+                    const int mi = i * FN + j;
+                    if (st == 0 && mi == 48) {
+                        // my reads of tile kt are done (both its buffers may be refilled) and my loads of tile
+                        // kt+1 have landed: everything but the 8 youngest requests (B rows of tile kt+2)
+                        __builtin_amdgcn_sched_barrier(0);
+                        __builtin_amdgcn_s_waitcnt(vmcnt_lgkm0_imm(HL));
+                        lds_barrier();
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[st][j], fa[st][i], acc[i][j], 0, 0, 0);
+                    if (mi < 32 && (mi & 1) == 0) {       // 16 fragment reads, one per two MFMAs
+                        const int r = mi >> 1;
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (r < FN) read_frag_b(b_rd, st ^ 1, r, st ^ 1);
+                        else read_frag_a(a_rd, st ^ 1, r - FN, st ^ 1);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    if (st == 0 && mi >= 48 && (mi & 1) == 0) {       // A rows of tile kt+2 into the buffer just left
+                        __builtin_amdgcn_sched_barrier(0);
+                        load_a((mi - 48) >> 1, t2, a_cur);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    if (st == 1 && mi >= 32 && (mi & 3) == 0) {       // B rows of tile kt+3 into tile kt's buffer
+                        __builtin_amdgcn_sched_barrier(0);
+                        load_b((mi - 32) >> 2, t3, b_cur);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
+            __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_waitcnt(0xC07F);           // next step's fragments are in registers
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        b_cur = b_nxt;
+    }
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));             // clamped tail requests still target this block's LDS
+    asm volatile("" ::: "memory");                        // keep the epilogue's loads out of the main loop
     store_tile16<FM, FN, TM, TN, SWIGLU>(p, t, acc, wm, wn, lane);
 }
 
@@ -880,12 +1072,21 @@ static hipError_t launch_ring(const GemmArgs& a, int max_mtiles, hipStream_t s)
 }
 
 template <bool SWIGLU>
+static hipError_t launch_w4(const GemmArgs& a, int max_mtiles, hipStream_t s)
+{
+    constexpr int LDS = 160 * 1024;
+    static bool attr_set = false;
+    return launch_tiles(ffn_gemm_w4_kernel<SWIGLU>, attr_set, 256, LDS, SWIGLU ? 128 : 256, a, max_mtiles, s);
+}
+
+template <bool SWIGLU>
 static hipError_t dispatch_gemm(int BM, const GemmArgs& a, int max_mtiles, hipStream_t s)
 {
     switch (BM) {
         case 256:
             if (std::getenv("BROWNOUT_MOE_PP")) return launch_pp<256, 64, 2, SWIGLU>(a, max_mtiles, s);
             if (std::getenv("BROWNOUT_MOE_RING")) return launch_ring<256, SWIGLU>(a, max_mtiles, s);
+            if (SWIGLU && std::getenv("BROWNOUT_MOE_W4")) return launch_w4<SWIGLU>(a, max_mtiles, s);
             return launch_rs<256, SWIGLU>(a, max_mtiles, s);
         case 128: return launch_pp<128, 64, 3, SWIGLU>(a, max_mtiles, s);
         case 64: return launch_small<64, 256, 1, 4, 64, 3, SWIGLU>(a, max_mtiles, s);
