@@ -125,7 +125,7 @@ def main():
         achieved = flops_gemm1 / (gemm1_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None}
-    roofline["kernel"] = "ffn_gemm_kernel<SWIGLU> (GEMM1)"
+    roofline["kernel"] = "GEMM1 (ffn_gemm_*_kernel<SWIGLU>)"
     roofline["kernel_ms"] = gemm1_ms
     # HBM bytes of one GEMM1 launch as counted by rocprofv3 (FETCH_SIZE + WRITE_SIZE, scaled by a copy
     # probe): taken from the committed profile summary of this workload, if there is one

@@ -83,7 +83,8 @@ Workspace carve_workspace(const Dims& D)
     W.tiles1 = take(16 + (size_t)D.tile_cap * 16);
     W.h_rows = D.row_cap;
     W.y_rows = D.row_cap * D.ksplit > 2 * (int64_t)D.T ? D.row_cap * D.ksplit : 2 * (int64_t)D.T;
-    W.H = take((size_t)W.h_rows * D.Fmax * 2);
+    // one tile of rows past the end: GEMM2's ragged last tile reads (and discards) whole tiles of H
+    W.H = take((size_t)(W.h_rows + 256) * D.Fmax * 2);
     W.Y = take((size_t)W.y_rows * D.d * 2);
     W.ones = take((size_t)D.T * 4);
     W.total = o;

@@ -92,6 +92,7 @@ struct GemmArgs {
     int n_ntiles;
     int group_m;                                // M tiles per L2 super-tile
     int ksplit; long plane;                     // GEMM2 only: K split into ksplit slices, slice s writes out + s*plane
+    int a_fits_32;                              // every byte offset into A fits 32 bits (gathered A rows)
 };
 
 // Workgroup barrier that orders LDS traffic for the compiler without the vmcnt(0) wait __syncthreads()
@@ -227,6 +228,10 @@ __device__ __forceinline__ void store_tile16(const GemmArgs& p, const Tile& t, c
                                              int wn, int lane)
 {
     unsigned short* out = reinterpret_cast<unsigned short*>(p.out) + (size_t)t.kslice * p.plane;
+    // A zero the compiler cannot see through: it keeps the row-weight loads below from being hoisted above
+    // the main loop, where their registers are not available.
+    int zero;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(zero));
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
         const int rl = wm * TM + i * 16 + (lane & 15);
@@ -247,7 +252,7 @@ __device__ __forceinline__ void store_tile16(const GemmArgs& p, const Tile& t, c
                         make_uint2((unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16));
             }
         } else {
-            const float w = p.row_weight[t.row0 + rl];
+            const float w = p.row_weight[t.row0 + rl + zero];
 #pragma unroll
             for (int j = 0; j < FN; ++j) {
                 const int col = t.n0 + wn * TN + j * 16 + 4 * (lane >> 4);
@@ -702,16 +707,31 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);
     const int r8 = lane >> 3;
     const int csw = (lane & 7) ^ ((((wave & 1) << 2) + (r8 >> 1)) & 7);
-    unsigned offA[HL];
+    // GEMM1 gathers its A rows (tokens of the unit); GEMM2 reads consecutive rows of H, which is padded by
+    // one tile of rows so that the rows of a ragged tile need no clamping.
+    constexpr bool GATHER = SWIGLU;
+    unsigned offA[GATHER ? HL : 1];
+    if (GATHER) {
 #pragma unroll
-    for (int i = 0; i < HL; ++i) {
-        const int row = (wave + i * NW) * RPG + r8;
-        const int r = row < t.nrows ? row : 0;
-        const long src_row = p.gather ? (long)p.gather[t.row0 + r] : (long)(t.row0 + r);
-        offA[i] = (unsigned)(src_row * p.lda * 2 + csw * 16);
+        for (int i = 0; i < HL; ++i) {
+            const int row = (wave + i * NW) * RPG + r8;
+            const int r = row < t.nrows ? row : 0;
+            const long src_row = p.gather ? (long)p.gather[t.row0 + r] : (long)(t.row0 + r);
+            offA[GATHER ? i : 0] = (unsigned)(src_row * p.lda * 2 + csw * 16);
+        }
+    } else {
+        offA[0] = (unsigned)((long)r8 * p.lda * 2 + csw * 16);
     }
     const unsigned offB = (unsigned)((long)r8 * p.K * 2 + csw * 16);
-    const bf16_t* baseA = uniform_ptr(p.A + (size_t)k_first * BK);
+    const bf16_t* baseA[GATHER ? 1 : HL];
+    if (GATHER) {
+        baseA[0] = uniform_ptr(p.A + (size_t)k_first * BK);
+    } else {
+#pragma unroll
+        for (int i = 0; i < HL; ++i)
+            baseA[GATHER ? 0 : i] =
+                uniform_ptr(p.A + (size_t)(t.row0 + (wave_s + i * NW) * RPG) * p.lda + (size_t)k_first * BK);
+    }
     const bf16_t* baseB[HL];
 #pragma unroll
     for (int q = 0; q < HL; ++q) {
@@ -730,7 +750,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
     }
     // one direct load: 8 rows x 128 bytes into 1 KiB of LDS
     auto load_a = [&](int i, int tile, int abuf) {
-        const char* src = reinterpret_cast<const char*>(baseA + (long)tile * BK) + offA[i];
+        const char* src = reinterpret_cast<const char*>(baseA[GATHER ? 0 : i] + (long)tile * BK) + offA[GATHER ? i : 0];
         char* dst = smem + abuf * ABUF + (wave_s + i * NW) * 1024;
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                          (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
@@ -786,6 +806,12 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
     for (int j = 0; j < FN; ++j) read_frag_b(0, 0, j, 0);
     __builtin_amdgcn_s_waitcnt(0xC07F);
 
+    // pin the accumulators to the accumulation registers on both sides of the loop: left to itself the
+    // register allocator sometimes trades them against the fragments and spills
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) asm volatile("" : "+a"(acc[i][j]));
     int b_cur = 0;                                        // B buffer of tile kt (kt mod 3)
     for (int kt = 0; kt < nk; ++kt) {
         const int a_cur = kt & 1;
@@ -835,7 +861,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
         b_cur = b_nxt;
     }
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));             // clamped tail requests still target this block's LDS
-    asm volatile("" ::: "memory");                        // keep the epilogue's loads out of the main loop
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) asm volatile("" : "+a"(acc[i][j]));
     store_tile16<FM, FN, TM, TN, SWIGLU>(p, t, acc, wm, wn, lane);
 }
 
@@ -1086,8 +1115,8 @@ static hipError_t dispatch_gemm(int BM, const GemmArgs& a, int max_mtiles, hipSt
         case 256:
             if (std::getenv("BROWNOUT_MOE_PP")) return launch_pp<256, 64, 2, SWIGLU>(a, max_mtiles, s);
             if (std::getenv("BROWNOUT_MOE_RING")) return launch_ring<256, SWIGLU>(a, max_mtiles, s);
-            if (SWIGLU && std::getenv("BROWNOUT_MOE_W4")) return launch_w4<SWIGLU>(a, max_mtiles, s);
-            return launch_rs<256, SWIGLU>(a, max_mtiles, s);
+            if (!a.a_fits_32 || std::getenv("BROWNOUT_MOE_RS")) return launch_rs<256, SWIGLU>(a, max_mtiles, s);
+            return launch_w4<SWIGLU>(a, max_mtiles, s);
         case 128: return launch_pp<128, 64, 3, SWIGLU>(a, max_mtiles, s);
         case 64: return launch_small<64, 256, 1, 4, 64, 3, SWIGLU>(a, max_mtiles, s);
         default: return launch_small<32, 256, 1, 4, 64, 4, SWIGLU>(a, max_mtiles, s);
@@ -1117,6 +1146,7 @@ hipError_t launch_ffn(const Dims& D, int u_lo, int u_hi, int Fdim, int64_t expec
     if (const char* e = std::getenv("BROWNOUT_MOE_GM")) group_m = std::max(1, std::atoi(e));
     g1.group_m = group_m;
     g1.ksplit = 1; g1.plane = 0;
+    g1.a_fits_32 = (uint64_t)D.T * (uint64_t)D.d * 2 < (1ull << 32);
     {
         ProfScope ps(MOE_STAGE_GEMM1, s);
         hipError_t e = dispatch_gemm<true>(BM, g1, max_mtiles, s);
@@ -1131,6 +1161,7 @@ hipError_t launch_ffn(const Dims& D, int u_lo, int u_hi, int Fdim, int64_t expec
     g2.n_ntiles = 0;
     g2.group_m = group_m;
     g2.ksplit = D.ksplit; g2.plane = D.y_plane;
+    g2.a_fits_32 = 1;                           // rows of H are addressed relative to the tile
     {
         ProfScope ps(MOE_STAGE_GEMM2, s);
         hipError_t e = dispatch_gemm<false>(BM, g2, max_mtiles, s);
