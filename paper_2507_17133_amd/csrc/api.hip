@@ -318,18 +318,18 @@ moe_status moe_forward(const moe_config* cfg, const void* x, int32_t T, const fl
     bf16_t* Y = at<bf16_t>(workspace, W.Y);
     const int64_t rows_per_expert = (int64_t)T * D.K / D.m;
     if (D.Ns > 0 && D.Fs != D.F) {
-        e = launch_ffn(D, 0, D.m + D.G, D.F, rows_per_expert, xb, R.row_token, R.unit_cnt, R.unit_off, R.row_weight,
+        e = launch_ffn(D, 0, D.m + D.G, D.F, rows_per_expert, xb, R.row_token, R.unit_cnt, R.unit_off,
                        fe, fu, fs, at<int32_t>(workspace, W.tiles0), H, Y, s);
         if (e != hipSuccess) return hip_fail(e, "moe_forward/ffn");
-        e = launch_ffn(D, D.m + D.G, D.U, D.Fs, T, xb, R.row_token, R.unit_cnt, R.unit_off, R.row_weight, fe, fu, fs,
+        e = launch_ffn(D, D.m + D.G, D.U, D.Fs, T, xb, R.row_token, R.unit_cnt, R.unit_off, fe, fu, fs,
                        at<int32_t>(workspace, W.tiles1), H, Y, s);
         if (e != hipSuccess) return hip_fail(e, "moe_forward/ffn_shared");
     } else {
-        e = launch_ffn(D, 0, D.U, D.F, rows_per_expert, xb, R.row_token, R.unit_cnt, R.unit_off, R.row_weight, fe, fu,
+        e = launch_ffn(D, 0, D.U, D.F, rows_per_expert, xb, R.row_token, R.unit_cnt, R.unit_off, fe, fu,
                        fs, at<int32_t>(workspace, W.tiles0), H, Y, s);
         if (e != hipSuccess) return hip_fail(e, "moe_forward/ffn");
     }
-    e = launch_combine(D, xb, Y, R.token_rows, static_cast<bf16_t*>(out), s);
+    e = launch_combine(D, xb, Y, R.token_rows, R.row_weight, static_cast<bf16_t*>(out), s);
     if (e != hipSuccess) return hip_fail(e, "moe_forward/combine");
     return MOE_OK;
 }
@@ -385,7 +385,7 @@ moe_status moe_build_united(const moe_config* cfg, const moe_ffn_weights* expert
     auto run_unit = [&](int u, bf16_t* Y) -> hipError_t {
         hipError_t err = launch_single_unit(unit_cnt, unit_off, D.U, u, n_calib, ones, s);
         if (err != hipSuccess) return err;
-        return launch_ffn(D, u, u + 1, D.F, n_calib, xb, nullptr, unit_cnt, unit_off, ones, fe, fu, fs, tiles, H, Y, s);
+        return launch_ffn(D, u, u + 1, D.F, n_calib, xb, nullptr, unit_cnt, unit_off, fe, fu, fs, tiles, H, Y, s);
     };
     for (int g = 0; g < G; ++g) {
         const int lo = g * way, hi = lo + way < m ? lo + way : m;

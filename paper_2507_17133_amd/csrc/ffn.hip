@@ -1,8 +1,8 @@
 // Expert FFNs of the BrownoutMoE layer as two grouped GEMMs on gfx950 MFMA, plus the weighted combine.
 //
 //   GEMM1  H[r][f] = silu(x_r . W1_u[f]) * (x_r . W3_u[f])      rows r of unit u, gathered from x
-//   GEMM2  Y[r][c] = row_weight[r] * (H_r . W2_u[c])
-//   combine out_t  = [x_t] + sum over the token's rows of Y      (layer equation, fixed order)
+//   GEMM2  Y[r][c] = H_r . W2_u[c]                              (stored in half precision)
+//   combine out_t  = [x_t] + sum over the token's rows r of row_weight[r] * Y_r   (layer equation, fixed order)
 //
 // Both operands of both GEMMs are K-contiguous (x [T][d], W1/W3 [F][d], H [R][F], W2 [d][F]), which is
 // the natural operand order of v_mfma_f32_32x32x16_bf16: a lane supplies 8 consecutive k of one row.
@@ -35,6 +35,28 @@ __device__ __forceinline__ unsigned short f2bf(float f)
     return (unsigned short)(u >> 16);
 }
 __device__ __forceinline__ float bf2f(unsigned short b) { return __uint_as_float(((unsigned int)b) << 16); }
+// two floats -> two bf16 (round to nearest even) in one 32-bit word, first value in the low half
+__device__ __forceinline__ unsigned pack_bf16(float lo, float hi)
+{
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    const f32x2 v = {lo, hi};
+    const bf16x2 b = __builtin_convertvector(v, bf16x2);
+    return __builtin_bit_cast(unsigned, b);
+}
+// Two floats -> two IEEE half values in one 32-bit word (round toward zero, so an overflow saturates at
+// the largest finite half instead of becoming infinite).  Y, the FFN output rows between GEMM2 and the
+// combine, is stored this way: the combine adds up rows of different experts that partly cancel, and with
+// bf16's 8-bit mantissa the rounding of the large terms would dominate the error of the small sum.
+__device__ __forceinline__ unsigned pack_f16(float lo, float hi)
+{
+    return __builtin_bit_cast(unsigned, __builtin_amdgcn_cvt_pkrtz(lo, hi));
+}
+// silu(g) * u with the hardware exp2 and reciprocal (the result is rounded to bf16 right after)
+__device__ __forceinline__ float swiglu(float g, float u)
+{
+    return g * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504f * g)) * u;
+}
 
 // ------------------------------------------------------------------------------------------------
 // Tile table: header {n_mtiles, 0, 0, 0} then one int4 {unit, first row, rows, 0} per M tile, units in
@@ -88,7 +110,6 @@ struct GemmArgs {
     int m, G;
     int N, K;                                   // GEMM1: N = F (columns of W1 and of W3), GEMM2: N = d
     bf16_t* out; long ldo;
-    const float* row_weight;
     int n_ntiles;
     int group_m;                                // M tiles per L2 super-tile
     int ksplit; long plane;                     // GEMM2 only: K split into ksplit slices, slice s writes out + s*plane
@@ -191,30 +212,23 @@ __device__ __forceinline__ void store_tile(const GemmArgs& p, const Tile& t, con
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int col = t.n0 + (wn * (TN / 64) + jp) * 32 + 8 * q + 4 * (lane >> 5);
-                    unsigned short h[4];
+                    float h[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float g = acc[i][2 * jp][4 * q + e], u = acc[i][2 * jp + 1][4 * q + e];
-                        h[e] = f2bf(g * __frcp_rn(1.0f + __expf(-g)) * u);
-                    }
+                    for (int e = 0; e < 4; ++e) h[e] = swiglu(acc[i][2 * jp][4 * q + e], acc[i][2 * jp + 1][4 * q + e]);
                     if (col < p.N)
-                        *reinterpret_cast<uint2*>(orow + col) =
-                            make_uint2((unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16));
+                        *reinterpret_cast<uint2*>(orow + col) = make_uint2(pack_bf16(h[0], h[1]), pack_bf16(h[2], h[3]));
                 }
             }
         } else {
-            const float w = p.row_weight[t.row0 + rl];
 #pragma unroll
             for (int j = 0; j < FN; ++j) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int col = t.n0 + wn * TN + j * 32 + 8 * q + 4 * (lane >> 5);
-                    unsigned short h[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) h[e] = f2bf(acc[i][j][4 * q + e] * w);
                     if (col < p.N)
                         *reinterpret_cast<uint2*>(orow + col) =
-                            make_uint2((unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16));
+                            make_uint2(pack_f16(acc[i][j][4 * q], acc[i][j][4 * q + 1]),
+                                       pack_f16(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]));
                 }
             }
         }
@@ -222,46 +236,45 @@ __device__ __forceinline__ void store_tile(const GemmArgs& p, const Tile& t, con
 }
 
 // Epilogue for 16x16 MFMA tiles (same transposed product): a lane holds, for output row lane&15, the four
-// consecutive columns 4*(lane>>4) + 0..3 of each 16x16 tile.
+// consecutive columns 4*(lane>>4) + 0..3 of each 16x16 tile.  All values are converted first, as one
+// branch-free block the scheduler can interleave freely (a lone wave per SIMD has nothing else to hide
+// the latency of exp and rcp behind), then stored row by row under the row mask.  N is a multiple of 64,
+// so a 64-column group of a wave tile is either entirely inside the matrix or entirely outside.
 template <int FM, int FN, int TM, int TN, bool SWIGLU>
 __device__ __forceinline__ void store_tile16(const GemmArgs& p, const Tile& t, const f32x4 (&acc)[FM][FN], int wm,
                                              int wn, int lane)
 {
     unsigned short* out = reinterpret_cast<unsigned short*>(p.out) + (size_t)t.kslice * p.plane;
-    // A zero the compiler cannot see through: it keeps the row-weight loads below from being hoisted above
-    // the main loop, where their registers are not available.
-    int zero;
-    asm volatile("v_mov_b32 %0, 0" : "=v"(zero));
+    constexpr int NG = SWIGLU ? FN / 2 : FN;             // 8-byte stores per output row and wave
+    constexpr int HM = FM / 2;
 #pragma unroll
-    for (int i = 0; i < FM; ++i) {
-        const int rl = wm * TM + i * 16 + (lane & 15);
-        if (rl >= t.nrows) continue;
-        unsigned short* orow = out + (long)(t.row0 + rl) * p.ldo;
-        if (SWIGLU) {
+    for (int half = 0; half < 2; ++half) {
+        uint2 res[HM][NG];
 #pragma unroll
-            for (int jp = 0; jp < FN / 2; ++jp) {
-                const int col = t.n0 + (wn * (TN / 32) + jp) * 16 + 4 * (lane >> 4);
-                unsigned short h[4];
+        for (int ii = 0; ii < HM; ++ii) {
+            const int i = half * HM + ii;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float g = acc[i][2 * jp][e], u = acc[i][2 * jp + 1][e];
-                    h[e] = f2bf(g * __frcp_rn(1.0f + __expf(-g)) * u);
+            for (int g = 0; g < NG; ++g) {
+                if (SWIGLU) {
+                    float h[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) h[e] = swiglu(acc[i][2 * g][e], acc[i][2 * g + 1][e]);
+                    res[ii][g] = make_uint2(pack_bf16(h[0], h[1]), pack_bf16(h[2], h[3]));
+                } else {
+                    res[ii][g] = make_uint2(pack_f16(acc[i][g][0], acc[i][g][1]), pack_f16(acc[i][g][2], acc[i][g][3]));
                 }
-                if (col < p.N)
-                    *reinterpret_cast<uint2*>(orow + col) =
-                        make_uint2((unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16));
             }
-        } else {
-            const float w = p.row_weight[t.row0 + rl + zero];
+        }
 #pragma unroll
-            for (int j = 0; j < FN; ++j) {
-                const int col = t.n0 + wn * TN + j * 16 + 4 * (lane >> 4);
-                unsigned short h[4];
+        for (int ii = 0; ii < HM; ++ii) {
+            const int i = half * HM + ii;
+            const int rl = wm * TM + i * 16 + (lane & 15);
+            if (rl >= t.nrows) continue;
+            unsigned short* orow = out + (long)(t.row0 + rl) * p.ldo;
 #pragma unroll
-                for (int e = 0; e < 4; ++e) h[e] = f2bf(acc[i][j][e] * w);
-                if (col < p.N)
-                    *reinterpret_cast<uint2*>(orow + col) =
-                        make_uint2((unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16));
+            for (int g = 0; g < NG; ++g) {
+                const int cbase = SWIGLU ? t.n0 + (wn * (TN / 32) + g) * 16 : t.n0 + wn * TN + g * 16;
+                if (cbase < p.N) *reinterpret_cast<uint2*>(orow + cbase + 4 * (lane >> 4)) = res[ii][g];
             }
         }
     }
@@ -669,16 +682,49 @@ __global__ void __launch_bounds__(512) ffn_gemm_rs_kernel(GemmArgs p)
 
 // ------------------------------------------------------------------------------------------------
 // Four-wave kernel (256 x 256 x 64 block tile, one wave per SIMD, wave tile 128 x 128, 16x16x32 MFMA,
-// accumulators in the accumulation registers).  One instruction stream per SIMD feeds the matrix pipe
-// without hand-offs: a k tile is two steps of 64 MFMAs, and between the MFMAs of a step the wave reads
-// the next step's fragments from LDS (double-buffered in registers) and issues direct global->LDS loads.
-// The 160 KiB of LDS hold two buffers for the A rows (activations, mostly L2 hits) and three for the B
-// rows (weights, which stream from memory and need the longer lead).  One barrier per k tile, three
-// quarters into its first step, when a wave has read its last fragments of tile kt and its loads of tile
-// kt+1 have landed; right after it the A rows of tile kt+2 are requested into the buffer just left, and
-// in the second step the B rows of tile kt+3.  Requests past the end of K are clamped to the last tile
-// (never read).
+// accumulators in the accumulation registers), persistent: one block per CU walks over its tiles.
+// One instruction stream per SIMD feeds the matrix pipe without hand-offs: a k tile is two steps of 64
+// MFMAs, and between the MFMAs of a step the wave reads the next step's fragments from LDS
+// (double-buffered in registers) and issues direct global->LDS loads.  The 160 KiB of LDS hold two
+// buffers for the A rows (activations, mostly L2 hits) and three for the B rows (weights, which stream
+// from memory and need the longer lead).  One barrier per k tile, three quarters into its first step,
+// when a wave has read its last fragments of tile kt and its loads of tile kt+1 have landed; right after
+// it the A rows of tile kt+2 are requested into the buffer just left, and in the second step the B rows
+// of tile kt+3.  Requests past the end of K are clamped to the last k tile (never read).
+// Between output tiles: the gather indices of the next tile are fetched during the main loop, its first
+// k tiles are requested before the epilogue of the current tile, so they land while that runs.
+// Blocks b, b+8, ... share an XCD; block b takes the tiles xcd*chunk + slot, + slots, ... of its XCD's
+// contiguous chunk, so the blocks of an XCD sweep its chunk together.
 // ------------------------------------------------------------------------------------------------
+template <int BNC>
+__device__ __forceinline__ bool decode_tile_at(const GemmArgs& p, int xcd, int bi, Tile& t)
+{
+    const int n_mt = p.table[0];
+    const int tiles = n_mt * p.n_ntiles;
+    const int total = tiles * p.ksplit;
+    const int chunk = (total + 7) >> 3;
+    if (bi >= chunk) return false;
+    const int Lfull = xcd * chunk + bi;
+    if (Lfull >= total) return false;
+    t.kslice = Lfull / tiles;
+    const int L = Lfull - t.kslice * tiles;
+    const int gspan = p.group_m * p.n_ntiles;
+    const int gi = L / gspan, rem = L - gi * gspan;
+    const int mt_first = gi * p.group_m;
+    const int gsz = min(p.group_m, n_mt - mt_first);
+    t.nt = rem / gsz;
+    const int mt = mt_first + (rem - t.nt * gsz);
+    const int4 te = reinterpret_cast<const int4*>(p.table + 4)[mt];
+    t.unit = te.x; t.row0 = te.y; t.nrows = te.z;
+    const int src = t.unit < p.m ? 0 : (t.unit < p.m + p.G ? 1 : 2);
+    const int widx = t.unit - (src == 0 ? 0 : (src == 1 ? p.m : p.m + p.G));
+    const size_t wsz = (size_t)p.N * p.K;
+    t.Wa = (src == 0 ? p.wa0 : (src == 1 ? p.wa1 : p.wa2)) + (size_t)widx * wsz;
+    t.Wb = p.wb0 ? (src == 0 ? p.wb0 : (src == 1 ? p.wb1 : p.wb2)) + (size_t)widx * wsz : nullptr;
+    t.n0 = t.nt * BNC;
+    return true;
+}
+
 template <bool SWIGLU>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) ffn_gemm_w4_kernel(GemmArgs p)
 {
@@ -689,65 +735,74 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
     constexpr int ABUF = BM * RB, BBUF = BN * RB;        // 32 KiB each
     constexpr int B_BASE = 2 * ABUF;
     constexpr int HL = BM / RPG / NW;                    // 8 loads of A rows and 8 of B rows per wave and tile
-    static_assert(2 * ABUF + 3 * BBUF <= 160 * 1024, "LDS budget of one CU");
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-
-    Tile t;
-    if (!decode_tile<SWIGLU ? BN / 2 : BN, SWIGLU>(p, t)) return;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    int k_first, nk;
-    k_range<BK>(p, t, k_first, nk);
-
-    // Load i of a wave covers rows (wave + 4 i) * 8 .. + 8 of the A (or B) tile.  An address is a
-    // wave-uniform base (scalar registers) plus a 32-bit lane offset: A rows are gathered, so each load has
-    // its own lane offset from the start of A; the B rows of a load are 8 consecutive weight rows, so all
-    // B loads share one lane offset.  The swizzle term ((row/2)&7) is the same for every load of a lane
-    // because (wave + 4 i) * 4 == 4 * (wave & 1) (mod 8).
-    const int wave_s = __builtin_amdgcn_readfirstlane(wave);
-    const int r8 = lane >> 3;
-    const int csw = (lane & 7) ^ ((((wave & 1) << 2) + (r8 >> 1)) & 7);
+    constexpr int BNC = SWIGLU ? BN / 2 : BN;
     // GEMM1 gathers its A rows (tokens of the unit); GEMM2 reads consecutive rows of H, which is padded by
     // one tile of rows so that the rows of a ragged tile need no clamping.
     constexpr bool GATHER = SWIGLU;
-    unsigned offA[GATHER ? HL : 1];
-    if (GATHER) {
-#pragma unroll
-        for (int i = 0; i < HL; ++i) {
-            const int row = (wave + i * NW) * RPG + r8;
-            const int r = row < t.nrows ? row : 0;
-            const long src_row = p.gather ? (long)p.gather[t.row0 + r] : (long)(t.row0 + r);
-            offA[GATHER ? i : 0] = (unsigned)(src_row * p.lda * 2 + csw * 16);
-        }
-    } else {
-        offA[0] = (unsigned)((long)r8 * p.lda * 2 + csw * 16);
-    }
+    constexpr int NOA = GATHER ? HL : 1, NBA = GATHER ? 1 : HL;
+    static_assert(2 * ABUF + 3 * BBUF <= 160 * 1024, "LDS budget of one CU");
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    const int xcd = blockIdx.x & 7, slots = gridDim.x >> 3;
+    int bi = blockIdx.x >> 3;
+    Tile t;
+    if (!decode_tile_at<BNC>(p, xcd, bi, t)) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+    const int wm = wave >> 1, wn = wave & 1;
+
+    // Load i of a wave covers rows (wave + 4 i) * 8 .. + 8 of the A (or B) tile.  An address is a
+    // wave-uniform base (scalar registers) plus a 32-bit lane offset: gathered A rows have one lane offset
+    // per load from the start of A; consecutive A rows (GEMM2) and the B rows of a load are 8 consecutive
+    // rows, so one lane offset serves all loads and the base moves.  The swizzle term ((row/2)&7) is the
+    // same for every load of a lane because (wave + 4 i) * 4 == 4 * (wave & 1) (mod 8).
+    const int r8 = lane >> 3;
+    const int csw = (lane & 7) ^ ((((wave & 1) << 2) + (r8 >> 1)) & 7);
     const unsigned offB = (unsigned)((long)r8 * p.K * 2 + csw * 16);
-    const bf16_t* baseA[GATHER ? 1 : HL];
-    if (GATHER) {
-        baseA[0] = uniform_ptr(p.A + (size_t)k_first * BK);
-    } else {
-#pragma unroll
-        for (int i = 0; i < HL; ++i)
-            baseA[GATHER ? 0 : i] =
-                uniform_ptr(p.A + (size_t)(t.row0 + (wave_s + i * NW) * RPG) * p.lda + (size_t)k_first * BK);
-    }
+    unsigned offA[NOA];
+    const bf16_t* baseA[NBA];
     const bf16_t* baseB[HL];
+    int nk = 0, last = 0;
+
+    // Source rows of the 64 A rows this wave loads per k tile (gathered A only), one per lane: lane k holds
+    // the row behind load k/8, row k%8; the loads pick theirs up with a cross-lane read in setup_tile.
+    auto gather_rows = [&](const Tile& tt) -> int {
+        const int row = (wave + (lane >> 3) * NW) * RPG + (lane & 7);
+        const int r = row < tt.nrows ? row : 0;          // ragged tiles re-read row 0; such rows are never stored
+        return p.gather ? p.gather[tt.row0 + r] : tt.row0 + r;
+    };
+    auto setup_tile = [&](const Tile& tt, int grows) {
+        int k_first;
+        k_range<BK>(p, tt, k_first, nk);
+        last = nk - 1;
+        if (GATHER) {
 #pragma unroll
-    for (int q = 0; q < HL; ++q) {
-        const int g = wave_s + NW * q;                    // 8-row group inside the B tile, 0..31
-        const bf16_t* W = t.Wa;
-        int col0;
-        if (SWIGLU) {
-            const int w_n = g >> 4, j16 = (g & 15) >> 1;
-            col0 = t.n0 + (w_n * 4 + (j16 >> 1)) * 16 + (g & 1) * 8;
-            if (j16 & 1) W = t.Wb;
+            for (int i = 0; i < HL; ++i)
+                offA[GATHER ? i : 0] = (unsigned)((long)__shfl(grows, i * 8 + r8) * p.lda * 2 + csw * 16);
+            baseA[0] = uniform_ptr(p.A + (size_t)k_first * BK);
         } else {
-            col0 = t.n0 + g * 8;
+            offA[0] = (unsigned)((long)r8 * p.lda * 2 + csw * 16);
+#pragma unroll
+            for (int i = 0; i < HL; ++i)
+                baseA[GATHER ? 0 : i] =
+                    uniform_ptr(p.A + (size_t)(tt.row0 + (wave_s + i * NW) * RPG) * p.lda + (size_t)k_first * BK);
         }
-        col0 = min(col0, p.N - 8);                        // columns past N are never stored
-        baseB[q] = uniform_ptr(W + (size_t)col0 * p.K + (size_t)k_first * BK);
-    }
+#pragma unroll
+        for (int q = 0; q < HL; ++q) {
+            const int g = wave_s + NW * q;                // 8-row group inside the B tile, 0..31
+            const bf16_t* W = tt.Wa;
+            int col0;
+            if (SWIGLU) {
+                const int w_n = g >> 4, j16 = (g & 15) >> 1;
+                col0 = tt.n0 + (w_n * 4 + (j16 >> 1)) * 16 + (g & 1) * 8;
+                if (j16 & 1) W = tt.Wb;
+            } else {
+                col0 = tt.n0 + g * 8;
+            }
+            col0 = min(col0, p.N - 8);                    // columns past N are never stored
+            baseB[q] = uniform_ptr(W + (size_t)col0 * p.K + (size_t)k_first * BK);
+        }
+    };
     // one direct load: 8 rows x 128 bytes into 1 KiB of LDS
     auto load_a = [&](int i, int tile, int abuf) {
         const char* src = reinterpret_cast<const char*>(baseA[GATHER ? 0 : i] + (long)tile * BK) + offA[GATHER ? i : 0];
@@ -761,36 +816,23 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                          (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
     };
+    // first k tiles of an output tile: tiles 0 and 1, and the B rows of tile 2 (5 * HL loads)
+    auto issue_prologue = [&]() {
+#pragma unroll
+        for (int i = 0; i < HL; ++i) load_a(i, 0, 0);
+#pragma unroll
+        for (int q = 0; q < HL; ++q) load_b(q, 0, 0);
+#pragma unroll
+        for (int i = 0; i < HL; ++i) load_a(i, min(1, last), 1);
+#pragma unroll
+        for (int q = 0; q < HL; ++q) load_b(q, min(1, last), 1);
+#pragma unroll
+        for (int q = 0; q < HL; ++q) load_b(q, min(2, last), 2);
+    };
 
-    f32x4 acc[FM][FN];
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.0f;
-    if (nk <= 0) {
-        store_tile16<FM, FN, TM, TN, SWIGLU>(p, t, acc, wm, wn, lane);
-        return;
-    }
-    const int last = nk - 1;
-    // prologue: tiles 0 and 1, and the B rows of tile 2
-#pragma unroll
-    for (int i = 0; i < HL; ++i) load_a(i, 0, 0);
-#pragma unroll
-    for (int q = 0; q < HL; ++q) load_b(q, 0, 0);
-#pragma unroll
-    for (int i = 0; i < HL; ++i) load_a(i, min(1, last), 1);
-#pragma unroll
-    for (int q = 0; q < HL; ++q) load_b(q, min(1, last), 1);
-#pragma unroll
-    for (int q = 0; q < HL; ++q) load_b(q, min(2, last), 2);
     const int a_off = (wm * TM + (lane & 15)) * RB;
     const int b_off = B_BASE + (wn * TN + (lane & 15)) * RB;
     const int swz = ((lane & 15) / L::WR) & (L::CPR - 1);
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(3 * HL));        // tile 0 has landed
-    lds_barrier();
-
     bf16x8 fa[2][FM], fb[2][FN];
     auto read_frag_a = [&](int abuf, int half, int i, int buf) {
         const int sw = ((half * 4 + (lane >> 4)) ^ swz) << 4;
@@ -800,72 +842,120 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
         const int sw = ((half * 4 + (lane >> 4)) ^ swz) << 4;
         fb[buf][j] = *reinterpret_cast<const bf16x8*>(smem + bbuf * BBUF + b_off + j * 16 * RB + sw);
     };
-#pragma unroll
-    for (int i = 0; i < FM; ++i) read_frag_a(0, 0, i, 0);
-#pragma unroll
-    for (int j = 0; j < FN; ++j) read_frag_b(0, 0, j, 0);
-    __builtin_amdgcn_s_waitcnt(0xC07F);
 
-    // pin the accumulators to the accumulation registers on both sides of the loop: left to itself the
-    // register allocator sometimes trades them against the fragments and spills
+    setup_tile(t, GATHER ? gather_rows(t) : 0);
+    issue_prologue();
+
+    for (;;) {
+        // the next output tile of this block, or this one again when there is none (its index load is
+        // issued either way, so the number of loads in flight does not depend on it)
+        Tile tn;
+        const bool has_next = decode_tile_at<BNC>(p, xcd, bi + slots, tn);
+        if (!has_next) tn = t;
+        const int gnext = GATHER ? gather_rows(tn) : 0;
+
+        f32x4 acc[FM][FN];
 #pragma unroll
-    for (int i = 0; i < FM; ++i)
+        for (int i = 0; i < FM; ++i)
 #pragma unroll
-        for (int j = 0; j < FN; ++j) asm volatile("" : "+a"(acc[i][j]));
-    int b_cur = 0;                                        // B buffer of tile kt (kt mod 3)
-    for (int kt = 0; kt < nk; ++kt) {
-        const int a_cur = kt & 1;
-        const int b_nxt = b_cur == 2 ? 0 : b_cur + 1;
-        const int t2 = min(kt + 2, last), t3 = min(kt + 3, last);
+            for (int j = 0; j < FN; ++j)
 #pragma unroll
-        for (int st = 0; st < 2; ++st) {
-            // fragments of the next step: second half of this tile, or first half of the next tile
-            const int a_rd = st == 0 ? a_cur : a_cur ^ 1;
-            const int b_rd = st == 0 ? b_cur : b_nxt;
+                for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.0f;
+        // pin the accumulators to the accumulation registers on both sides of the loop: left to itself the
+        // register allocator sometimes trades them against the fragments and spills
 #pragma unroll
-            for (int i = 0; i < FM; ++i)
+        for (int i = 0; i < FM; ++i)
 #pragma unroll
-                for (int j = 0; j < FN; ++j) {
-                    const int mi = i * FN + j;
-                    if (st == 0 && mi == 48) {
-                        // my reads of tile kt are done (both its buffers may be refilled) and my loads of tile
-                        // kt+1 have landed: everything but the 8 youngest requests (B rows of tile kt+2)
-                        __builtin_amdgcn_sched_barrier(0);
-                        __builtin_amdgcn_s_waitcnt(vmcnt_lgkm0_imm(HL));
-                        lds_barrier();
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[st][j], fa[st][i], acc[i][j], 0, 0, 0);
-                    if (mi < 32 && (mi & 1) == 0) {       // 16 fragment reads, one per two MFMAs
-                        const int r = mi >> 1;
-                        __builtin_amdgcn_sched_barrier(0);
-                        if (r < FN) read_frag_b(b_rd, st ^ 1, r, st ^ 1);
-                        else read_frag_a(a_rd, st ^ 1, r - FN, st ^ 1);
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                    if (st == 0 && mi >= 48 && (mi & 1) == 0) {       // A rows of tile kt+2 into the buffer just left
-                        __builtin_amdgcn_sched_barrier(0);
-                        load_a((mi - 48) >> 1, t2, a_cur);
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                    if (st == 1 && mi >= 32 && (mi & 3) == 0) {       // B rows of tile kt+3 into tile kt's buffer
-                        __builtin_amdgcn_sched_barrier(0);
-                        load_b((mi - 32) >> 2, t3, b_cur);
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
+            for (int j = 0; j < FN; ++j) asm volatile("" : "+a"(acc[i][j]));
+
+        if (nk > 0) {
+            // k tile 0 has landed once at most the 3 * HL younger loads of the first batch, and the index
+            // loads after them, are in flight (stores of the previous epilogue only make this wait longer)
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(3 * HL + (GATHER ? 1 : 0)));
+            lds_barrier();
+#pragma unroll
+            for (int i = 0; i < FM; ++i) read_frag_a(0, 0, i, 0);
+#pragma unroll
+            for (int j = 0; j < FN; ++j) read_frag_b(0, 0, j, 0);
+            __builtin_amdgcn_s_waitcnt(0xC07F);
+
+            int b_cur = 0;                                // B buffer of tile kt (kt mod 3)
+            for (int kt = 0; kt < nk; ++kt) {
+                const int a_cur = kt & 1;
+                const int b_nxt = b_cur == 2 ? 0 : b_cur + 1;
+                const int t2 = min(kt + 2, last), t3 = min(kt + 3, last);
+#pragma unroll
+                for (int st = 0; st < 2; ++st) {
+                    // fragments of the next step: second half of this tile, or first half of the next tile
+                    const int a_rd = st == 0 ? a_cur : a_cur ^ 1;
+                    const int b_rd = st == 0 ? b_cur : b_nxt;
+#pragma unroll
+                    for (int i = 0; i < FM; ++i)
+#pragma unroll
+                        for (int j = 0; j < FN; ++j) {
+                            const int mi = i * FN + j;
+                            if (st == 0 && mi == 48) {
+                                // my reads of tile kt are done (both its buffers may be refilled) and my loads
+                                // of tile kt+1 have landed: everything but the HL youngest requests
+                                __builtin_amdgcn_sched_barrier(0);
+                                __builtin_amdgcn_s_waitcnt(vmcnt_lgkm0_imm(HL));
+                                lds_barrier();
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                            acc[i][j] =
+                                __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[st][j], fa[st][i], acc[i][j], 0, 0, 0);
+                            if (mi < 32 && (mi & 1) == 0) {       // 16 fragment reads, one per two MFMAs
+                                const int r = mi >> 1;
+                                __builtin_amdgcn_sched_barrier(0);
+                                if (r < FN) read_frag_b(b_rd, st ^ 1, r, st ^ 1);
+                                else read_frag_a(a_rd, st ^ 1, r - FN, st ^ 1);
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                            if (st == 0 && mi >= 48 && (mi & 1) == 0) {   // A rows of tile kt+2 into the buffer just left
+                                __builtin_amdgcn_sched_barrier(0);
+                                load_a((mi - 48) >> 1, t2, a_cur);
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                            if (st == 1 && mi >= 32 && (mi & 3) == 0) {   // B rows of tile kt+3 into tile kt's buffer
+                                __builtin_amdgcn_sched_barrier(0);
+                                load_b((mi - 32) >> 2, t3, b_cur);
+                                __builtin_amdgcn_sched_barrier(0);
+                            }
+                        }
+                    __builtin_amdgcn_sched_barrier(0);
+                    __builtin_amdgcn_s_waitcnt(0xC07F);   // next step's fragments are in registers
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-            __builtin_amdgcn_sched_barrier(0);
-            __builtin_amdgcn_s_waitcnt(0xC07F);           // next step's fragments are in registers
-            __builtin_amdgcn_sched_barrier(0);
+                b_cur = b_nxt;
+            }
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));     // clamped tail requests still target this block's LDS
+            lds_barrier();                                // everyone has left the LDS buffers
         }
-        b_cur = b_nxt;
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j) asm volatile("" : "+a"(acc[i][j]));
+
+        // the index load has returned by now (all loads were waited for above); saying so here keeps the
+        // compiler from waiting for it, and with it for the next tile's first loads, inside the epilogue
+        asm volatile("" ::"v"(gnext));
+        const Tile tcur = t;
+        if (has_next) {
+            // request the first k tiles of the next output tile, then let them land behind the epilogue
+            t = tn;
+            bi += slots;
+            setup_tile(t, gnext);
+            issue_prologue();
+        }
+        {
+            // lane-derived epilogue values are recomputed per tile instead of living through the main loop
+            int lane_e;
+            asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(lane_e));
+            store_tile16<FM, FN, TM, TN, SWIGLU>(p, tcur, acc, wave_s >> 1, wave_s & 1, lane_e);
+        }
+        if (!has_next) break;
     }
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));             // clamped tail requests still target this block's LDS
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j) asm volatile("" : "+a"(acc[i][j]));
-    store_tile16<FM, FN, TM, TN, SWIGLU>(p, t, acc, wm, wn, lane);
+    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1010,7 +1100,8 @@ __global__ void __launch_bounds__(512) ffn_gemm_ring_kernel(GemmArgs p)
 // combine: one thread = 8 columns of one token; rows summed in slot order, shared experts first.
 // ------------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) combine_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ Y,
-                                                      const int32_t* __restrict__ token_rows, bf16_t* __restrict__ out,
+                                                      const int32_t* __restrict__ token_rows,
+                                                      const float* __restrict__ row_weight, bf16_t* __restrict__ out,
                                                       int T, int d, int K, int Ns, int add_residual, int ksplit, long plane)
 {
     const int chunks = d >> 3;
@@ -1020,30 +1111,49 @@ __global__ void __launch_bounds__(256) combine_kernel(const bf16_t* __restrict__
     float acc[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
-    auto add_row = [&](const bf16_t* rowp) {
+    typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+    auto add_row = [&](const bf16_t* rowp, float (&a)[8]) {                 // a row of x (bf16)
         const uint4 q = *reinterpret_cast<const uint4*>(rowp + c8);
         const unsigned int w[4] = {q.x, q.y, q.z, q.w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            acc[2 * e] += __uint_as_float(w[e] << 16);
-            acc[2 * e + 1] += __uint_as_float(w[e] & 0xFFFF0000u);
+            a[2 * e] += __uint_as_float(w[e] << 16);
+            a[2 * e + 1] += __uint_as_float(w[e] & 0xFFFF0000u);
         }
     };
-    if (add_residual) add_row(x + (long)t * d);
+    auto add_y_row = [&](const bf16_t* rowp, float (&a)[8]) {               // a row of Y (half precision)
+        const uint4 q = *reinterpret_cast<const uint4*>(rowp + c8);
+        const unsigned int w[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const f16x2 h = __builtin_bit_cast(f16x2, w[e]);
+            a[2 * e] += (float)h[0];
+            a[2 * e + 1] += (float)h[1];
+        }
+    };
+    // one row of the FFN output: its K-split planes summed in order, then times the row's weight
+    auto add_ffn_row = [&](int r) {
+        float part[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) part[e] = 0.0f;
+        for (int q = 0; q < ksplit; ++q) add_y_row(Y + q * plane + (long)r * d, part);
+        const float w = row_weight[r];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] += w * part[e];
+    };
+    if (add_residual) add_row(x + (long)t * d, acc);
     const int slots = K + Ns;
     const int32_t* tr = token_rows + (long)t * slots;
-    for (int s = 0; s < Ns; ++s)
-        for (int q = 0; q < ksplit; ++q) add_row(Y + q * plane + (long)tr[K + s] * d);
+    for (int s = 0; s < Ns; ++s) add_ffn_row(tr[K + s]);
     for (int j = 0; j < K; ++j) {
         const int r = tr[j];
-        if (r >= 0)
-            for (int q = 0; q < ksplit; ++q) add_row(Y + q * plane + (long)r * d);
+        if (r >= 0) add_ffn_row(r);
     }
     uint4 o;
-    o.x = (unsigned)f2bf(acc[0]) | ((unsigned)f2bf(acc[1]) << 16);
-    o.y = (unsigned)f2bf(acc[2]) | ((unsigned)f2bf(acc[3]) << 16);
-    o.z = (unsigned)f2bf(acc[4]) | ((unsigned)f2bf(acc[5]) << 16);
-    o.w = (unsigned)f2bf(acc[6]) | ((unsigned)f2bf(acc[7]) << 16);
+    o.x = pack_bf16(acc[0], acc[1]);
+    o.y = pack_bf16(acc[2], acc[3]);
+    o.z = pack_bf16(acc[4], acc[5]);
+    o.w = pack_bf16(acc[6], acc[7]);
     *reinterpret_cast<uint4*>(out + (long)t * d + c8) = o;
 }
 
@@ -1105,7 +1215,27 @@ static hipError_t launch_w4(const GemmArgs& a, int max_mtiles, hipStream_t s)
 {
     constexpr int LDS = 160 * 1024;
     static bool attr_set = false;
-    return launch_tiles(ffn_gemm_w4_kernel<SWIGLU>, attr_set, 256, LDS, SWIGLU ? 128 : 256, a, max_mtiles, s);
+    static int n_cu = 0;
+    auto kern = ffn_gemm_w4_kernel<SWIGLU>;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        if (e != hipSuccess) return e;
+        int dev = 0;
+        e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    GemmArgs g = a;
+    g.n_ntiles = ceil_div(g.N, SWIGLU ? 128 : 256);
+    const long total = (long)max_mtiles * g.n_ntiles * g.ksplit;
+    // one block per CU (the LDS footprint allows no second one), a multiple of 8 so every XCD has the same
+    // number of blocks; fewer when there cannot be that many tiles
+    const int grid = (int)std::min<long>((total + 7) / 8 * 8, std::max(8, n_cu / 8 * 8));
+    kern<<<grid, 256, LDS, s>>>(g);
+    return hipGetLastError();
 }
 
 template <bool SWIGLU>
@@ -1125,7 +1255,7 @@ static hipError_t dispatch_gemm(int BM, const GemmArgs& a, int max_mtiles, hipSt
 
 hipError_t launch_ffn(const Dims& D, int u_lo, int u_hi, int Fdim, int64_t expected_rows, const bf16_t* x,
                       const int32_t* gather, const int32_t* unit_cnt, const int32_t* unit_off,
-                      const float* row_weight, const FfnWeights& experts, const FfnWeights& united,
+                      const FfnWeights& experts, const FfnWeights& united,
                       const FfnWeights& shared, int32_t* tile_table, bf16_t* H, bf16_t* Y, hipStream_t s)
 {
     const int n_units = u_hi - u_lo;
@@ -1140,7 +1270,7 @@ hipError_t launch_ffn(const Dims& D, int u_lo, int u_hi, int Fdim, int64_t expec
     g1.wa0 = experts.w1; g1.wa1 = united.w1; g1.wa2 = shared.w1;
     g1.wb0 = experts.w3; g1.wb1 = united.w3; g1.wb2 = shared.w3;
     g1.m = D.m; g1.G = D.G; g1.N = Fdim; g1.K = D.d;
-    g1.out = H; g1.ldo = D.Fmax; g1.row_weight = nullptr;
+    g1.out = H; g1.ldo = D.Fmax;
     g1.n_ntiles = 0;                            // set by launch_gemm from its tile width
     int group_m = 4;
     if (const char* e = std::getenv("BROWNOUT_MOE_GM")) group_m = std::max(1, std::atoi(e));
@@ -1157,7 +1287,7 @@ hipError_t launch_ffn(const Dims& D, int u_lo, int u_hi, int Fdim, int64_t expec
     g2.wa0 = experts.w2; g2.wa1 = united.w2; g2.wa2 = shared.w2;
     g2.wb0 = g2.wb1 = g2.wb2 = nullptr;
     g2.m = D.m; g2.G = D.G; g2.N = D.d; g2.K = Fdim;
-    g2.out = Y; g2.ldo = D.d; g2.row_weight = row_weight;
+    g2.out = Y; g2.ldo = D.d;
     g2.n_ntiles = 0;
     g2.group_m = group_m;
     g2.ksplit = D.ksplit; g2.plane = D.y_plane;
@@ -1170,12 +1300,12 @@ hipError_t launch_ffn(const Dims& D, int u_lo, int u_hi, int Fdim, int64_t expec
     return hipSuccess;
 }
 
-hipError_t launch_combine(const Dims& D, const bf16_t* x, const bf16_t* Y, const int32_t* token_rows, bf16_t* out,
-                          hipStream_t s)
+hipError_t launch_combine(const Dims& D, const bf16_t* x, const bf16_t* Y, const int32_t* token_rows,
+                          const float* row_weight, bf16_t* out, hipStream_t s)
 {
     ProfScope ps(MOE_STAGE_COMBINE, s);
     const long n = (long)D.T * (D.d / 8);
-    combine_kernel<<<(int)((n + 255) / 256), 256, 0, s>>>(x, Y, token_rows, out, D.T, D.d, D.K, D.Ns, D.add_residual,
+    combine_kernel<<<(int)((n + 255) / 256), 256, 0, s>>>(x, Y, token_rows, row_weight, out, D.T, D.d, D.K, D.Ns, D.add_residual,
                                                           D.ksplit, D.y_plane);
     return hipGetLastError();
 }

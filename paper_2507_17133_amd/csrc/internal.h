@@ -43,7 +43,7 @@ struct Workspace {
     size_t seg_cnt, seg_off;                          // [n_seg][U] int32
     size_t tiles0, tiles1;                            // two GEMM tile tables: int32[4] header + int4 entries
     size_t H;                                         // [h_rows][Fmax] bf16
-    size_t Y;                                         // [y_rows][d] bf16
+    size_t Y;                                         // [y_rows][d], IEEE half (2 bytes; carried as bf16_t*)
     size_t ones;                                      // [T] fp32 (build_united)
     size_t total;
     int64_t h_rows, y_rows;
@@ -74,14 +74,14 @@ hipError_t launch_route(const Dims& D, const bf16_t* x, const float* gate_w, con
 // ---- FFN (ffn.hip) ----
 struct FfnWeights { const bf16_t *w1, *w3, *w2; };
 // Runs W2(silu(W1 x)*(W3 x)) for the rows of units [u_lo,u_hi) listed in (unit_cnt, unit_off, gather),
-// writes Y[row][d] = row_weight[row] * FFN(x[gather ? gather[row] : row]).  Fdim is the FFN width of
+// writes Y[row][d] = FFN(x[gather ? gather[row] : row]) (the row weights are applied by the combine).  Fdim is the FFN width of
 // these units.  Weight source of unit u: u<m experts[u]; u<m+G united[u-m]; else shared[u-m-G].
 hipError_t launch_ffn(const Dims& D, int u_lo, int u_hi, int Fdim, int64_t expected_rows, const bf16_t* x,
                       const int32_t* gather, const int32_t* unit_cnt, const int32_t* unit_off,
-                      const float* row_weight, const FfnWeights& experts, const FfnWeights& united,
+                      const FfnWeights& experts, const FfnWeights& united,
                       const FfnWeights& shared, int32_t* tile_table, bf16_t* H, bf16_t* Y, hipStream_t s);
 hipError_t launch_combine(const Dims& D, const bf16_t* x, const bf16_t* Y, const int32_t* token_rows,
-                          bf16_t* out, hipStream_t s);
+                          const float* row_weight, bf16_t* out, hipStream_t s);
 
 // ---- united experts (united.hip) ----
 hipError_t launch_united_mean(const bf16_t* w, int m, int way, size_t n_elem, bf16_t* u, hipStream_t s);

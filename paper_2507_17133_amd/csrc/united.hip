@@ -80,7 +80,8 @@ __global__ void __launch_bounds__(1024) sqdiff_kernel(const unsigned short* __re
     __shared__ double red[16];
     double s = 0.0;
     for (size_t e = threadIdx.x; e < n; e += 1024) {
-        const float df = __uint_as_float(((unsigned int)a[e]) << 16) - __uint_as_float(((unsigned int)b[e]) << 16);
+        // FFN output rows are stored in half precision
+        const float df = (float)__builtin_bit_cast(_Float16, a[e]) - (float)__builtin_bit_cast(_Float16, b[e]);
         s += (double)df * (double)df;
     }
 #pragma unroll
