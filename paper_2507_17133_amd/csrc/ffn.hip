@@ -688,9 +688,9 @@ __global__ void __launch_bounds__(512) ffn_gemm_rs_kernel(GemmArgs p)
 // (double-buffered in registers) and issues direct global->LDS loads.  The 160 KiB of LDS hold two
 // buffers for the A rows (activations, mostly L2 hits) and three for the B rows (weights, which stream
 // from memory and need the longer lead).  One barrier per k tile, three quarters into its first step,
-// when a wave has read its last fragments of tile kt and its loads of tile kt+1 have landed; right after
-// it the A rows of tile kt+2 are requested into the buffer just left, and in the second step the B rows
-// of tile kt+3.  Requests past the end of K are clamped to the last k tile (never read).
+// when a wave has read its last fragments of tile kt and its loads of tile kt+1 have landed; from there
+// on one load is issued every eight MFMAs: first the A rows of tile kt+2 into the buffer just left, then
+// the B rows of tile kt+3.  Requests past the end of K are clamped to the last k tile (never read).
 // Between output tiles: the gather indices of the next tile are fetched during the main loop, its first
 // k tiles are requested before the epilogue of the current tile, so they land while that runs.
 // Blocks b, b+8, ... share an XCD; block b takes the tiles xcd*chunk + slot, + slots, ... of its XCD's
@@ -816,7 +816,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                          (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
     };
-    // first k tiles of an output tile: tiles 0 and 1, and the B rows of tile 2 (5 * HL loads)
+    // first k tiles of an output tile: tiles 0 and 1, and the first two B loads of tile 2 (4 * HL + 2 loads)
     auto issue_prologue = [&]() {
 #pragma unroll
         for (int i = 0; i < HL; ++i) load_a(i, 0, 0);
@@ -827,7 +827,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
 #pragma unroll
         for (int q = 0; q < HL; ++q) load_b(q, min(1, last), 1);
 #pragma unroll
-        for (int q = 0; q < HL; ++q) load_b(q, min(2, last), 2);
+        for (int q = 0; q < 2; ++q) load_b(q, min(2, last), 2);
     };
 
     const int a_off = (wm * TM + (lane & 15)) * RB;
@@ -869,9 +869,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
             for (int j = 0; j < FN; ++j) asm volatile("" : "+a"(acc[i][j]));
 
         if (nk > 0) {
-            // k tile 0 has landed once at most the 3 * HL younger loads of the first batch, and the index
-            // loads after them, are in flight (stores of the previous epilogue only make this wait longer)
-            __builtin_amdgcn_s_waitcnt(vmcnt_imm(3 * HL + (GATHER ? 1 : 0)));
+            // k tile 0 has landed once at most the 2 * HL + 2 younger loads of the first batch, and the index
+            // load after them, are in flight (stores of the previous epilogue only make this wait longer)
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * HL + 2 + (GATHER ? 1 : 0)));
             lds_barrier();
 #pragma unroll
             for (int i = 0; i < FM; ++i) read_frag_a(0, 0, i, 0);
@@ -883,6 +883,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
             for (int kt = 0; kt < nk; ++kt) {
                 const int a_cur = kt & 1;
                 const int b_nxt = b_cur == 2 ? 0 : b_cur + 1;
+                const int b_nn = b_nxt == 2 ? 0 : b_nxt + 1;          // B buffer of tile kt+2 (= of tile kt-1)
                 const int t2 = min(kt + 2, last), t3 = min(kt + 3, last);
 #pragma unroll
                 for (int st = 0; st < 2; ++st) {
@@ -911,14 +912,17 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
                                 else read_frag_a(a_rd, st ^ 1, r - FN, st ^ 1);
                                 __builtin_amdgcn_sched_barrier(0);
                             }
-                            if (st == 0 && mi >= 48 && (mi & 1) == 0) {   // A rows of tile kt+2 into the buffer just left
+                            // One direct load every eight MFMAs (closer together they queue up in the texture
+                            // path and hold the wave).  After the barrier: the A rows of tile kt+2 into the A
+                            // buffer just left, then the B rows of tile kt+3 into tile kt's B buffer, the last six
+                            // of them during the first three quarters of the next tile's first step.
+                            if ((mi & 7) == 0) {
+                                const int slot = mi >> 3;
                                 __builtin_amdgcn_sched_barrier(0);
-                                load_a((mi - 48) >> 1, t2, a_cur);
-                                __builtin_amdgcn_sched_barrier(0);
-                            }
-                            if (st == 1 && mi >= 32 && (mi & 3) == 0) {   // B rows of tile kt+3 into tile kt's buffer
-                                __builtin_amdgcn_sched_barrier(0);
-                                load_b((mi - 32) >> 2, t3, b_cur);
+                                if (st == 0 && slot < 6) load_b(slot + 2, t2, b_nn);
+                                if (st == 0 && slot >= 6) load_a(slot - 6, t2, a_cur);
+                                if (st == 1 && slot < 6) load_a(slot + 2, t2, a_cur);
+                                if (st == 1 && slot >= 6) load_b(slot - 6, t3, b_cur);
                                 __builtin_amdgcn_sched_barrier(0);
                             }
                         }
