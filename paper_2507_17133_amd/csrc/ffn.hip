@@ -5,16 +5,20 @@
 //   combine out_t  = [x_t] + sum over the token's rows r of row_weight[r] * Y_r   (layer equation, fixed order)
 //
 // Both operands of both GEMMs are K-contiguous (x [T][d], W1/W3 [F][d], H [R][F], W2 [d][F]), which is
-// the natural operand order of v_mfma_f32_32x32x16_bf16: a lane supplies 8 consecutive k of one row.
-// A block owns a BM x BN output tile; tiles of 64 k are staged global -> registers -> LDS (16-byte
-// chunks, XOR-swizzled so that both the 16-byte stores and the ds_read_b128 fragment loads are
-// conflict free), double buffered with one barrier per k tile.  In GEMM1 a block's BN columns are
-// BN/2 columns of W1 and the same BN/2 columns of W3, interleaved 32 by 32, so that the gate and up
+// the natural operand order of the bf16 MFMAs: a lane supplies 8 consecutive k of one row.  A block owns a
+// BM x 256 output tile; k tiles of 64 (whole 128-byte lines per row) are staged in LDS in 16-byte chunks,
+// XOR-swizzled so that the ds_read_b128 fragment loads are conflict free.  In GEMM1 a block's 256 B rows
+// are 128 columns of W1 and the same 128 columns of W3, interleaved tile by tile, so that the gate and up
 // values of one (row, f) land in the same lane and SwiGLU is applied in registers.
-// Which (unit, rows) an M tile covers comes from a tile table built on the device from the unit
-// counts, so skewed expert loads need no host round trip; the grid is an upper bound and surplus
-// blocks exit.  Block ids are remapped so that each XCD (block id mod 8) works on a contiguous range
-// of tiles and shares weight panels in its own L2.
+// Which (unit, rows) an M tile covers comes from a tile table built on the device from the unit counts,
+// so skewed expert loads need no host round trip.  Each XCD (block id mod 8) works on a contiguous range
+// of tiles, ordered so that the blocks it runs at a time share A and B panels in its own L2.
+//
+// Kernels, by tile height (chosen on the host from the expected rows per unit):
+//   256 rows  ffn_gemm_w4_kernel   four waves, one per SIMD, 128x128 wave tiles, 16x16x32 MFMA, persistent
+//             ffn_gemm_rs_kernel   eight waves, register-staged; stand-in when A offsets exceed 32 bits
+//   128 rows  ffn_gemm_pp_kernel   eight waves in two groups that alternate memory and MFMA phases
+//   64, 32    ffn_gemm_kernel      four waves, plain multi-stage ring (decode: weight streaming bound)
 #include "internal.h"
 
 #include <algorithm>
@@ -963,144 +967,6 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
 }
 
 // ------------------------------------------------------------------------------------------------
-// Ring kernel (BM x 256, 8 waves as 2 x 4, same ping-pong): k tiles of 64 are requested as whole 128-byte
-// lines by direct global->LDS loads, but live in LDS as two half-tiles of 32 k (64-byte rows) that are
-// consumed, and freed, one per step.  Five half-tile slots form a ring, so the two halves of tile kt+2
-// can be requested while tile kt is multiplied and tile kt+1 is landing: a request has at least a full
-// tile time to return although only 2.5 tiles fit in LDS.  The two loads of one row group (first and
-// second half of the same lines) are issued back to back.  Group 1 issues its loads in the first compute
-// phase of a tile, group 0 in the second; past the end of K loads are clamped to the last tile and land
-// in slots nobody reads any more.
-// ------------------------------------------------------------------------------------------------
-template <int BM, bool SWIGLU>
-__global__ void __launch_bounds__(512) ffn_gemm_ring_kernel(GemmArgs p)
-{
-    constexpr int BN = 256, WN = 4, NW = 8, HK = 32, RING = 5;
-    using L = Lds<HK>;
-    constexpr int TM = BM / 2, TN = BN / WN, FM = TM / 32, FN = TN / 32;
-    constexpr int RB = L::RB, RPG = L::RPG;
-    constexpr int STAGE = (BM + BN) * RB;
-    constexpr int GROUPS = (BM + BN) / RPG;
-    constexpr int GPW = GROUPS / NW;                     // row groups per wave; two loads each per tile
-    constexpr int NLD = 2 * GPW;
-    constexpr int NM = 2 * FM * FN;
-    constexpr int EV = NM / NLD > 0 ? NM / NLD : 1;
-    static_assert(GROUPS % NW == 0 && NLD <= NM, "loader shape");
-    static_assert(RING * STAGE <= 160 * 1024, "LDS budget of one CU");
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-
-    Tile t;
-    if (!decode_tile<SWIGLU ? BN / 2 : BN, SWIGLU>(p, t)) return;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wave_s = __builtin_amdgcn_readfirstlane(wave);
-    const int wm = wave >> 2, wn = wave & 3;
-    const int grp = wm;
-    int k_first, nk64;
-    k_range<64>(p, t, k_first, nk64);
-
-    const bf16_t* gptr[GPW];
-#pragma unroll
-    for (int i = 0; i < GPW; ++i) {
-        const int row = (wave + i * NW) * RPG + L::lane_row(lane);
-        const bf16_t* base = row < BM ? a_row_ptr(p, t, row) : b_row_ptr<TN, SWIGLU>(p, t, row - BM);
-        gptr[i] = base + L::lane_chunk(lane, row) * 8 + (size_t)k_first * 64;
-    }
-    f32x16 acc[FM][FN];
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-    if (nk64 <= 0) {
-        store_tile<FM, FN, TM, TN, SWIGLU>(p, t, acc, wm, wn, lane);
-        return;
-    }
-    const int nk = nk64, last = nk - 1;
-    // load j of tile kt: row group j/2, k half j%2, into ring slot s0 (first half) or s1 (second half)
-    auto issue = [&](int kt, int s0, int s1, int j) {
-        const int i = j >> 1, half = j & 1;
-        char* dst = smem + (half ? s1 : s0) * STAGE + (wave_s + i * NW) * 1024;
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(gptr[i] + (long)kt * 64 + half * HK),
-                                         (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
-    };
-#pragma unroll
-    for (int j = 0; j < NLD; ++j) issue(0, 0, 1, j);
-#pragma unroll
-    for (int j = 0; j < NLD; ++j) issue(min(1, last), 2, 3, j);
-    const int a_off = (wm * TM + (lane & 31)) * RB;
-    const int b_off = BM * RB + (wn * TN + (lane & 31)) * RB;
-    const int swz = L::read_swz(lane);
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(NLD));
-    lds_barrier();                                        // tile 0 is in LDS for everyone
-
-    auto main_loop = [&](auto grp_tag) {
-        constexpr int GRP = decltype(grp_tag)::value;
-        int r0 = 0;                                       // ring slot of the first half of tile kt
-        for (int kt = 0; kt < nk; ++kt) {
-            const int r1 = r0 + 1 == RING ? 0 : r0 + 1;
-            const int l0 = r0 + 4 >= RING ? r0 + 4 - RING : r0 + 4, l1 = r0;   // slots of tile kt+2's halves
-            const int lt = min(kt + 2, last);
-#pragma unroll
-            for (int ph = 0; ph < 2; ++ph) {
-                const char* St = smem + (ph == 0 ? r0 : r1) * STAGE;
-                bf16x8 af[2][FM], bfr[2][FN];
-#pragma unroll
-                for (int kk = 0; kk < 2; ++kk) {
-                    const int sw = ((kk * 2 + (lane >> 5)) ^ swz) << 4;
-#pragma unroll
-                    for (int i = 0; i < FM; ++i)
-                        af[kk][i] = *reinterpret_cast<const bf16x8*>(St + a_off + i * 32 * RB + sw);
-#pragma unroll
-                    for (int j = 0; j < FN; ++j)
-                        bfr[kk][j] = *reinterpret_cast<const bf16x8*>(St + b_off + j * 32 * RB + sw);
-                }
-                // group 1's last memory phase of tile kt is the last thing before group 0 reads tile kt+1:
-                // its loads of that tile (all but the youngest NLD) must have landed
-                if (GRP == 1 && ph == 1) __builtin_amdgcn_s_waitcnt(vmcnt_lgkm0_imm(NLD));
-                else __builtin_amdgcn_s_waitcnt(0xC07F);
-                __builtin_amdgcn_sched_barrier(0);
-                lds_barrier();
-                __builtin_amdgcn_sched_barrier(0);
-                const bool load_phase = GRP == 0 ? ph == 1 : ph == 0;
-                __builtin_amdgcn_s_setprio(1);
-#pragma unroll
-                for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-                    for (int i = 0; i < FM; ++i)
-#pragma unroll
-                        for (int j = 0; j < FN; ++j) {
-                            acc[i][j] =
-                                __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk][j], af[kk][i], acc[i][j], 0, 0, 0);
-                            const int mi = (kk * FM + i) * FN + j;
-                            if (load_phase && mi % EV == 0 && mi / EV < NLD) {
-                                __builtin_amdgcn_sched_barrier(0);
-                                issue(lt, l0, l1, mi / EV);
-                                __builtin_amdgcn_sched_barrier(0);
-                            }
-                        }
-                __builtin_amdgcn_s_setprio(0);
-                // group 0 ends tile kt right before it reads tile kt+1
-                if (GRP == 0 && ph == 1) __builtin_amdgcn_s_waitcnt(vmcnt_imm(NLD));
-                __builtin_amdgcn_sched_barrier(0);
-                lds_barrier();
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            r0 = r0 + 2 >= RING ? r0 + 2 - RING : r0 + 2;
-        }
-    };
-    if (grp == 0) {
-        main_loop(std::integral_constant<int, 0>{});
-        lds_barrier();
-    } else {
-        lds_barrier();
-        main_loop(std::integral_constant<int, 1>{});
-    }
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));             // clamped tail loads still target this block's LDS
-    store_tile<FM, FN, TM, TN, SWIGLU>(p, t, acc, wm, wn, lane);
-}
-
-// ------------------------------------------------------------------------------------------------
 // combine: one thread = 8 columns of one token; rows summed in slot order, shared experts first.
 // ------------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256) combine_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ Y,
@@ -1206,14 +1072,6 @@ static hipError_t launch_rs(const GemmArgs& a, int max_mtiles, hipStream_t s)
     return launch_tiles(ffn_gemm_rs_kernel<BM, SWIGLU>, attr_set, 512, LDS, SWIGLU ? 128 : 256, a, max_mtiles, s);
 }
 
-template <int BM, bool SWIGLU>
-static hipError_t launch_ring(const GemmArgs& a, int max_mtiles, hipStream_t s)
-{
-    constexpr int LDS = 5 * (BM + 256) * 32 * 2;
-    static bool attr_set = false;
-    return launch_tiles(ffn_gemm_ring_kernel<BM, SWIGLU>, attr_set, 512, LDS, SWIGLU ? 128 : 256, a, max_mtiles, s);
-}
-
 template <bool SWIGLU>
 static hipError_t launch_w4(const GemmArgs& a, int max_mtiles, hipStream_t s)
 {
@@ -1247,8 +1105,6 @@ static hipError_t dispatch_gemm(int BM, const GemmArgs& a, int max_mtiles, hipSt
 {
     switch (BM) {
         case 256:
-            if (std::getenv("BROWNOUT_MOE_PP")) return launch_pp<256, 64, 2, SWIGLU>(a, max_mtiles, s);
-            if (std::getenv("BROWNOUT_MOE_RING")) return launch_ring<256, SWIGLU>(a, max_mtiles, s);
             if (!a.a_fits_32 || std::getenv("BROWNOUT_MOE_RS")) return launch_rs<256, SWIGLU>(a, max_mtiles, s);
             return launch_w4<SWIGLU>(a, max_mtiles, s);
         case 128: return launch_pp<128, 64, 3, SWIGLU>(a, max_mtiles, s);
