@@ -36,6 +36,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=None)
     ap.add_argument("--stages", action="store_true", help="also print a per-kernel time breakdown to stderr")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also time the layer at thresholds 1.0 .. 0.0, partial and full brownout (to stderr)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy three times (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -145,6 +147,27 @@ def main():
         pr = P.profile_collect()
         P.profile_disable()
         log("  per-kernel ms (mean of 10): " + ", ".join(f"{k}={v[0]/max(1,v[1]):.4f}" for k, v in pr.items()))
+
+    if args.sweep:
+        # latency against the brownout threshold, 1.0 -> 0.0 in steps of 0.1, partial and full brownout
+        # (the grid of the paper's accuracy study, Results / Accuracy; here only the time side of it)
+        log(f"  threshold sweep ({cfg.name}, way {cfg.way}): threshold, ms/step partial (rows, active units), ms/step full")
+        for i in range(10, -1, -1):
+            thr = i / 10.0
+            res = []
+            for full in (False, True):
+                Rs = P.moe_route(c, L.x, L.gate_w, L.gate_b, thr, full, workspace=ws)
+                torch.cuda.synchronize()
+                rows_s, act_s = int(Rs.n_rows.item()), int((Rs.unit_cnt > 0).sum().item())
+                for _ in range(3):
+                    P.moe_forward(c, L.x, L.gate_w, L.gate_b, L.experts, united, L.shared, thr, full, None, out, ws)
+                torch.cuda.synchronize()
+                ts = time.perf_counter()
+                for _ in range(10):
+                    P.moe_forward(c, L.x, L.gate_w, L.gate_b, L.experts, united, L.shared, thr, full, None, out, ws)
+                torch.cuda.synchronize()
+                res.append(((time.perf_counter() - ts) * 100.0, rows_s, act_s))
+            log(f"    {thr:.1f}   {res[0][0]:8.3f} ({res[0][1]} rows, {res[0][2]} units)   {res[1][0]:8.3f} ({res[1][1]} rows, {res[1][2]} units)")
 
     cpu = None
     if not args.no_cpu_baseline:

@@ -64,6 +64,13 @@ CONFIGS = {
     "deepseek_v3": LayerConfig("deepseek_v3", T=16384, d=7168, F=2048, m=256, K=8, way=8,
                                n_shared=1, F_s=2048, score_fn=1, zipf_s=1.1,
                                brownout_fractions=(0.4, 0.0)),
+    # The paper's own evaluation model (Model and server configurations): 60 routed experts per layer.
+    # The other dimensions are those of the public Qwen1.5-MoE-A2.7B model card (hidden 2048, expert
+    # width 1408, top-4, one shared expert of width 5632; its sigmoid gate on the shared output is not
+    # modelled: the shared expert enters with weight 1).  way = 8 leaves a ragged last group of 4.
+    # The paper's (way, threshold) settings (2, 0), (4, 0.2), (8, 0.4) are fractions 1.0, 0.8, 0.6.
+    "qwen15_moe_a27b": LayerConfig("qwen15_moe_a27b", T=8192, d=2048, F=1408, m=60, K=4, way=8,
+                                   n_shared=1, F_s=5632, zipf_s=1.0, brownout_fractions=(0.6, 0.0)),
 }
 
 

@@ -27,6 +27,7 @@ CASES = [
     ("mixtral_decode", 0.0, 12), ("mixtral_decode", 0.5, 12), ("mixtral_decode", 1.0, 12),
     ("qwen3_30b_a3b", 0.5, 24), ("qwen3_30b_a3b", 0.0, 16),
     ("deepseek_v3", 0.4, 12),
+    ("qwen15_moe_a27b", 0.6, 24), ("qwen15_moe_a27b", 1.0, 16),
 ]
 
 
