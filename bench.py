@@ -38,6 +38,9 @@ def main():
     ap.add_argument("--stages", action="store_true", help="also print a per-kernel time breakdown to stderr")
     ap.add_argument("--sweep", action="store_true",
                     help="also time the layer at thresholds 1.0 .. 0.0, partial and full brownout (to stderr)")
+    ap.add_argument("--salc", action="store_true",
+                    help="also run the SLO-aware latency controller over a synthetic burst trace (to stderr)")
+    ap.add_argument("--salc-layers", type=int, default=24, help="MoE layers per serving iteration in --salc")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy three times (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -168,6 +171,40 @@ def main():
                 torch.cuda.synchronize()
                 res.append(((time.perf_counter() - ts) * 100.0, rows_s, act_s))
             log(f"    {thr:.1f}   {res[0][0]:8.3f} ({res[0][1]} rows, {res[0][2]} units)   {res[1][0]:8.3f} ({res[1][1]} rows, {res[1][2]} units)")
+
+    if args.salc:
+        # Algorithm 2 in a serving loop: the iteration time as a function of the threshold is measured here
+        # (args.salc_layers MoE layers per iteration), the request trace is synthetic (Poisson, rate doubling
+        # at 75 s of 250 s as in the paper's burst experiment, sized so that threshold 1 is at 45 % load before
+        # the burst and at 90 % after it), SLO = 3 x the iteration time without brownout.
+        from paper_2507_17133_amd import salc
+        thr_grid = [i / 10.0 for i in range(11)]
+        t_of = []
+        for thr in thr_grid:
+            for _ in range(3):
+                P.moe_forward(c, L.x, L.gate_w, L.gate_b, L.experts, united, L.shared, thr, False, None, out, ws)
+            torch.cuda.synchronize()
+            ts = time.perf_counter()
+            for _ in range(10):
+                P.moe_forward(c, L.x, L.gate_w, L.gate_b, L.experts, united, L.shared, thr, False, None, out, ws)
+            torch.cuda.synchronize()
+            t_of.append((time.perf_counter() - ts) / 10.0 * args.salc_layers)
+        tau = lambda thr: float(np.interp(thr, thr_grid, t_of))
+        tau1 = t_of[-1]
+        slo = 3.0 * tau1
+        lam = 0.45 / tau1
+        arr = salc.poisson_arrivals([(0.0, lam), (75.0, 2.0 * lam)], 250.0, seed=0)
+        fixed = salc.serve(arr, tau)
+        ctl = salc.serve(arr, tau, slo=slo)
+        log(f"  SALC trace ({cfg.name}, way {cfg.way}, {args.salc_layers} layers per iteration): iteration time "
+            f"{t_of[0]*1e3:.2f} ms at threshold 0 .. {tau1*1e3:.2f} ms at threshold 1; SLO {slo*1e3:.1f} ms; "
+            f"{len(arr)} requests, {lam:.1f}/s doubling at 75 s")
+        for nm, tr in (("threshold fixed at 1", fixed), ("SALC", ctl)):
+            lat = tr.latency[tr.arrival >= 75.0]
+            log(f"    {nm:22s}: SLO violations after the burst {salc.violation_rate(tr, slo, 75.0)*100:6.2f} %  "
+                f"(before {(tr.latency[tr.arrival < 75.0] > slo).mean()*100:5.2f} %), P90 latency after the burst "
+                f"{np.quantile(lat, 0.9)*1e3:8.1f} ms, mean threshold before / after "
+                f"{tr.threshold[tr.arrival < 75.0].mean():.3f} / {tr.threshold[tr.arrival >= 75.0].mean():.3f}")
 
     cpu = None
     if not args.no_cpu_baseline:

@@ -170,12 +170,37 @@ enum {
     MOE_STAGE_SCATTER = 4,/* row lists                                         */
     MOE_STAGE_TILES = 5,  /* GEMM tile table                                   */
     MOE_STAGE_GEMM1 = 6,  /* rows x [W1|W3] + SwiGLU                           */
-    MOE_STAGE_GEMM2 = 7,  /* H x W2, row weights                               */
+    MOE_STAGE_GEMM2 = 7,  /* H x W2                                            */
     MOE_STAGE_COMBINE = 8,/* weighted sum per token                            */
     MOE_N_STAGES = 9
 };
 moe_status moe_profile_enable(int32_t stage_mask);
 moe_status moe_profile_collect(double *total_ms /*[MOE_N_STAGES]*/, int64_t *launches /*[MOE_N_STAGES]*/);
+
+/*
+ * SLO-aware latency control (the paper's Algorithm 2, "SLO-Aware Latency
+ * Control Algorithm"): the host-side controller that moves `threshold`
+ * between calls of moe_forward.  Pure host functions, no device work, no state.
+ *
+ * moe_latency_p90: the P90 of n recent latencies (host array, any order, not
+ *   modified): the value of rank ceil(0.9 n) in ascending order.  NaN if
+ *   latencies is NULL or n is 0.
+ * moe_salc_update: one controller step.  With warning_line = slo *
+ *   warning_factor: latency below the warning line -> threshold + increment;
+ *   latency above slo -> threshold * shrink_ratio; otherwise unchanged.  The
+ *   result is clamped to [0, 1], the range moe_forward accepts (the paper does
+ *   not say what happens at the ends).  NaN if params is NULL, a field is not
+ *   finite, slo <= 0, warning_factor outside (0, 1], increment < 0 or
+ *   shrink_ratio outside [0, 1].
+ */
+typedef struct moe_salc_params {
+    double slo;            /* latency objective, same unit as the latencies */
+    double warning_factor; /* warning line as a fraction of slo (paper: 0.8) */
+    double increment;      /* additive step up (paper: 0.1)                 */
+    double shrink_ratio;   /* multiplicative step down (paper: 0.8)         */
+} moe_salc_params;
+double moe_latency_p90(const double *latencies, size_t n);
+double moe_salc_update(double threshold, double latency_p90, const moe_salc_params *params);
 
 #ifdef __cplusplus
 }

@@ -20,13 +20,17 @@ LIB_PATH = os.path.join(_HERE, "libbrownout_moe.so")
 MOE_OK = 0
 STAGES = ("prep", "gate", "count", "scan", "scatter", "tiles", "gemm1", "gemm2", "combine")
 EXPORTS = ("moe_status_string", "moe_last_hip_error", "moe_workspace_size", "moe_build_united", "moe_route",
-           "moe_forward", "moe_profile_enable", "moe_profile_collect")
+           "moe_forward", "moe_profile_enable", "moe_profile_collect", "moe_latency_p90", "moe_salc_update")
 
 
 class MoeError(RuntimeError):
     def __init__(self, status: int, where: str, detail: str = ""):
         self.status = status
         super().__init__(f"{where}: status {status} ({detail})")
+
+
+class moe_salc_params(C.Structure):
+    _fields_ = [(n, C.c_double) for n in ("slo", "warning_factor", "increment", "shrink_ratio")]
 
 
 class moe_config(C.Structure):
@@ -71,6 +75,10 @@ def lib():
                                   C.POINTER(moe_ffn_weights), C.POINTER(moe_ffn_weights), C.POINTER(moe_ffn_weights),
                                   C.c_double, C.c_int32, C.POINTER(moe_route_out), C.c_void_p, C.c_void_p, C.c_size_t,
                                   C.c_void_p]
+        L.moe_latency_p90.restype = C.c_double
+        L.moe_latency_p90.argtypes = [C.POINTER(C.c_double), C.c_size_t]
+        L.moe_salc_update.restype = C.c_double
+        L.moe_salc_update.argtypes = [C.c_double, C.c_double, C.POINTER(moe_salc_params)]
         L.moe_profile_enable.restype = C.c_int32
         L.moe_profile_enable.argtypes = [C.c_int32]
         L.moe_profile_collect.restype = C.c_int32
@@ -234,3 +242,18 @@ def profile_collect():
     n = (C.c_int64 * len(STAGES))()
     _check(lib().moe_profile_collect(ms, n), "moe_profile_collect")
     return {s: (float(ms[i]), int(n[i])) for i, s in enumerate(STAGES)}
+
+
+def latency_p90(latencies) -> float:
+    """P90 (nearest rank) of a sequence of host latencies, through the C ABI."""
+    n = len(latencies)
+    arr = (C.c_double * max(n, 1))(*[float(v) for v in latencies])
+    return float(lib().moe_latency_p90(arr if n else None, n))
+
+
+def salc_update(threshold: float, latency: float, slo: float, warning_factor: float = 0.8, increment: float = 0.1,
+                shrink_ratio: float = 0.8) -> float:
+    """One step of the SLO-aware latency controller (Algorithm 2), through the C ABI."""
+    p = moe_salc_params(slo, warning_factor, increment, shrink_ratio)
+    return float(lib().moe_salc_update(threshold, latency, C.byref(p)))
+
