@@ -47,6 +47,9 @@ SMALL = {
                            [1.0, 0.3]),
     "mid_tile": (WL.LayerConfig("mid_tile", T=600, d=128, F=256, m=8, K=2, way=4), [1.0, 0.5]),
     "multi_tile": (WL.LayerConfig("multi_tile", T=1500, d=256, F=384, m=4, K=2, way=4, zipf_s=1.2), [1.0, 0.7]),
+    # the largest K and number of shared experts the library accepts
+    "max_topk_max_shared": (WL.LayerConfig("max_topk_max_shared", T=48, d=64, F=64, m=64, K=32, way=8, n_shared=8,
+                                           F_s=64), [1.0, 0.5]),
 }
 
 
@@ -77,6 +80,36 @@ def test_route_and_forward(cfg, thr, full):
     e = rel_err(got, want)
     assert e <= OUT_TOL, f"max relative error {e}"
     assert torch.equal(out, out_r), "forward with a precomputed route must equal routing internally"
+
+
+def test_register_staged_kernel_for_wide_offsets(monkeypatch):
+    """The 256-row kernel that stands in when a byte offset into the gathered activations does not fit 32
+    bits (forced here through its switch: such a tensor would not fit a test)."""
+    cfg, thrs = SMALL["multi_tile"]
+    L, Lg = _layer(cfg)
+    c = P.config_of(cfg)
+    united_cpu = WL.make_random_united(cfg, 0, "cpu")
+    united = tuple(a.to(DEV) for a in united_cpu)
+    monkeypatch.setenv("BROWNOUT_MOE_RS", "1")
+    for thr in thrs:
+        ref = oracle_route(L, cfg, thr)
+        out = P.moe_forward(c, Lg.x, Lg.gate_w, Lg.gate_b, Lg.experts, united, Lg.shared, thr)
+        torch.cuda.synchronize()
+        want = O.forward_tokens(npf(L.x), ref.topk_idx, ref.topk_w, ref.expert_unit, cfg.way, npf(L.experts),
+                                npf(united_cpu), npf(L.shared))
+        assert rel_err(npf(out), want) <= OUT_TOL
+
+
+def test_empty_batch_is_rejected():
+    cfg = WL.CONFIGS["tiny"]
+    L, Lg = _layer(cfg)
+    c = P.config_of(cfg)
+    x0 = Lg.x[:0].contiguous()
+    with pytest.raises(P.MoeError) as ei:
+        P.moe_forward(c, x0, Lg.gate_w, Lg.gate_b, Lg.experts, None, None, 1.0,
+                      out=torch.empty((0, cfg.d), dtype=torch.bfloat16, device=DEV),
+                      workspace=P.alloc_workspace(c, 1, DEV))
+    assert ei.value.status == -1
 
 
 def test_residual():
