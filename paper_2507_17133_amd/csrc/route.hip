@@ -493,6 +493,44 @@ __device__ __forceinline__ void unit_offsets(const int32_t* unit_cnt, int U, int
     __syncthreads();
 }
 
+// Rows of token t (lane `lane` of its segment): off_s = first row of every unit, soff = rows of every unit
+// in earlier segments, bmw = the segment's token bitmaps.
+__device__ __forceinline__ void scatter_token(const RowArgs& p, const int* unit_s, const unsigned long long* bmw,
+                                              const int* off_s, const int32_t* soff, int t, int lane)
+{
+    const unsigned long long below = (1ull << lane) - 1ull;
+    const int32_t* idx = p.topk_idx + (size_t)t * p.K;
+    const float* wts = p.topk_w + (size_t)t * p.K;
+    const int slots = p.K + p.Ns;
+    for (int j = 0; j < p.K; ++j) {
+        const int u = unit_s[idx[j]];
+        int row = -1;
+        if (u >= 0) {
+            bool first = true;
+            if (u >= p.m)
+                for (int q = 0; q < j; ++q)
+                    if (unit_s[idx[q]] == u) first = false;
+            if (first) {
+                row = off_s[u] + soff[u] + __popcll(bmw[u] & below);
+                float w = wts[j];
+                if (u >= p.m)
+                    for (int q = j + 1; q < p.K; ++q)
+                        if (unit_s[idx[q]] == u) w += wts[q];     // merged entries, added in TopK order
+                p.row_token[row] = t;
+                p.row_weight[row] = w;
+            }
+        }
+        p.token_rows[(size_t)t * slots + j] = row;
+    }
+    for (int s = 0; s < p.Ns; ++s) {
+        const int u = p.m + p.G + s;
+        const int row = off_s[u] + soff[u] + __popcll(bmw[u] & below);
+        p.row_token[row] = t;
+        p.row_weight[row] = 1.0f;
+        p.token_rows[(size_t)t * slots + p.K + s] = row;
+    }
+}
+
 __global__ void __launch_bounds__(256) route_scatter_kernel(RowArgs p)
 {
     __shared__ int unit_s[kMaxExperts];
@@ -513,38 +551,63 @@ __global__ void __launch_bounds__(256) route_scatter_kernel(RowArgs p)
     mark_units(p, unit_s, bm[wave], t, lane);
     __syncthreads();
     if (t >= p.T) return;
-    const unsigned long long below = (1ull << lane) - 1ull;
-    const int32_t* idx = p.topk_idx + (size_t)t * p.K;
-    const float* wts = p.topk_w + (size_t)t * p.K;
-    const int slots = p.K + p.Ns;
-    const int32_t* soff = p.seg_off + (size_t)seg * p.U;
-    for (int j = 0; j < p.K; ++j) {
-        const int u = unit_s[idx[j]];
-        int row = -1;
-        if (u >= 0) {
-            bool first = true;
-            if (u >= p.m)
-                for (int q = 0; q < j; ++q)
-                    if (unit_s[idx[q]] == u) first = false;
-            if (first) {
-                row = off_s[u] + soff[u] + __popcll(bm[wave][u] & below);
-                float w = wts[j];
-                if (u >= p.m)
-                    for (int q = j + 1; q < p.K; ++q)
-                        if (unit_s[idx[q]] == u) w += wts[q];     // merged entries, added in TopK order
-                p.row_token[row] = t;
-                p.row_weight[row] = w;
-            }
+    scatter_token(p, unit_s, bm[wave], off_s, p.seg_off + (size_t)seg * p.U, t, lane);
+}
+
+// Small batches (at most 16 segments = 1024 tokens): Algorithm 1, the per-segment bitmaps, both scans and
+// the scatter in ONE block of 16 wavefronts, one segment per wavefront, everything in LDS.  Dynamic LDS:
+// bitmaps [16][U] (8 bytes) then segment offsets [16][U] (4 bytes).
+constexpr int kSmallSegs = 16;
+__global__ void __launch_bounds__(1024) route_small_kernel(RowArgs p)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char rsm[];
+    __shared__ int cnt_s[kMaxExperts];
+    __shared__ int unit_s[kMaxExperts];
+    __shared__ unsigned char s2_s[kMaxExperts];
+    __shared__ int ucnt_s[kMaxUnits];
+    __shared__ int off_s[kMaxUnits + 1];
+    unsigned long long* bm = reinterpret_cast<unsigned long long*>(rsm);                      // [16][U]
+    int* segoff = reinterpret_cast<int*>(rsm + (size_t)kSmallSegs * p.U * 8);                  // [16][U]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (tid < p.m) cnt_s[tid] = p.expert_cnt[tid];
+    for (int i = tid; i < kSmallSegs * p.U; i += 1024) bm[i] = 0ull;
+    __syncthreads();
+    brownout_decide(cnt_s, s2_s, unit_s, p.m, p.way, p.threshold, p.full, tid, true, p.expert_unit, p.expert_in_s1);
+    const int t = wave * kSegTokens + lane;
+    mark_units(p, unit_s, bm + (size_t)wave * p.U, t, lane);
+    __syncthreads();
+    for (int u = tid; u < p.U; u += 1024) {
+        int run = 0;
+        for (int sgm = 0; sgm < kSmallSegs; ++sgm) {
+            segoff[sgm * p.U + u] = run;
+            run += __popcll(bm[(size_t)sgm * p.U + u]);
         }
-        p.token_rows[(size_t)t * slots + j] = row;
+        ucnt_s[u] = run;
+        p.unit_cnt[u] = run;
     }
-    for (int s = 0; s < p.Ns; ++s) {
-        const int u = p.m + p.G + s;
-        const int row = off_s[u] + soff[u] + __popcll(bm[wave][u] & below);
-        p.row_token[row] = t;
-        p.row_weight[row] = 1.0f;
-        p.token_rows[(size_t)t * slots + p.K + s] = row;
+    __syncthreads();
+    if (wave == 0) {                                     // exclusive scan of the unit counts by one wavefront
+        const int per = (p.U + 63) / 64;
+        const int lo = min(p.U, lane * per), hi = min(p.U, lo + per);
+        int local = 0;
+        for (int u = lo; u < hi; ++u) local += ucnt_s[u];
+        int incl = local;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int o = __shfl_up(incl, off);
+            if (lane >= off) incl += o;
+        }
+        int run = incl - local;
+        for (int u = lo; u < hi; ++u) {
+            off_s[u] = run;
+            run += ucnt_s[u];
+        }
+        if (lane == 63) off_s[p.U] = incl;
     }
+    __syncthreads();
+    for (int u = tid; u <= p.U; u += 1024) p.unit_off[u] = off_s[u];
+    if (tid == 0 && p.n_rows) p.n_rows[0] = off_s[p.U];
+    if (t < p.T) scatter_token(p, unit_s, bm + (size_t)wave * p.U, off_s, segoff + wave * p.U, t, lane);
 }
 
 hipError_t launch_route(const Dims& D, const bf16_t* x, const float* gate_w, const float* gate_bias,
@@ -611,6 +674,18 @@ hipError_t launch_route(const Dims& D, const bf16_t* x, const float* gate_w, con
     p.full = full_brownout; p.threshold = threshold;
     p.seg_cnt = seg_cnt; p.seg_off = seg_off; p.unit_cnt = R.unit_cnt; p.unit_off = R.unit_off; p.n_rows = R.n_rows;
     p.row_token = R.row_token; p.row_weight = R.row_weight; p.token_rows = R.token_rows;
+    if (D.n_seg <= kSmallSegs) {
+        ProfScope ps(MOE_STAGE_COUNT, s);
+        static bool attr_set = false;
+        if (!attr_set) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(route_small_kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, kSmallSegs * kMaxUnits * 12);
+            if (e != hipSuccess) return e;
+            attr_set = true;
+        }
+        route_small_kernel<<<1, 1024, (size_t)kSmallSegs * D.U * 12, s>>>(p);
+        return hipGetLastError();
+    }
     const int seg_blocks = ceil_div(D.n_seg, 4);
     {
         ProfScope ps(MOE_STAGE_COUNT, s);
