@@ -41,6 +41,11 @@ def main():
     ap.add_argument("--salc", action="store_true",
                     help="also run the SLO-aware latency controller over a synthetic burst trace (to stderr)")
     ap.add_argument("--salc-layers", type=int, default=24, help="MoE layers per serving iteration in --salc")
+    ap.add_argument("--distill", action="store_true",
+                    help="also train the united experts by distillation on synthetic calibration tokens and compare "
+                         "the full-brownout layer output before and after (to stderr)")
+    ap.add_argument("--distill-steps", type=int, default=100)
+    ap.add_argument("--distill-tokens", type=int, default=2048)
     ap.add_argument("--copy-probe", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy three times (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -205,6 +210,30 @@ def main():
                 f"(before {(tr.latency[tr.arrival < 75.0] > slo).mean()*100:5.2f} %), P90 latency after the burst "
                 f"{np.quantile(lat, 0.9)*1e3:8.1f} ms, mean threshold before / after "
                 f"{tr.threshold[tr.arrival < 75.0].mean():.3f} / {tr.threshold[tr.arrival >= 75.0].mean():.3f}")
+
+    if args.distill:
+        # United Expert Model section: the student of every group is trained on calibration tokens (a seeded
+        # draw of the same distribution as x, other tokens) from the parameter mean; the layer output at
+        # threshold 0 (every multi-member group served by its united expert) is compared with the exact
+        # layer output before and after the training.
+        calib = WL.make_activations(cfg, 1, dev, name="calib", n=args.distill_tokens)
+        lr = 0.02 / float(np.sqrt(cfg.d))                # 2 % of the weights' standard deviation per step
+        exact = P.moe_forward(c, L.x, L.gate_w, L.gate_b, L.experts, united, L.shared, 1.0).float()
+        before = P.moe_forward(c, L.x, L.gate_w, L.gate_b, L.experts, united, L.shared, 0.0).float()
+        trained = tuple(u.clone() for u in united)
+        torch.cuda.synchronize()
+        ts = time.perf_counter()
+        hist = P.moe_distill_united(c, L.experts, trained, calib, args.distill_steps, lr)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - ts
+        after = P.moe_forward(c, L.x, L.gate_w, L.gate_b, L.experts, trained, L.shared, 0.0).float()
+        rel = lambda a: float(((a - exact).norm() / exact.norm()).item())
+        h = hist.cpu().numpy()
+        multi = [g for g in range(cfg.G) if min(cfg.m, (g + 1) * cfg.way) - g * cfg.way > 1]
+        log(f"  distillation ({cfg.name}, way {cfg.way}, {len(multi)} groups, {args.distill_tokens} calibration tokens, "
+            f"{args.distill_steps} Adam steps, lr {lr:.2e}): {dt:.2f} s = {dt/max(1,len(multi)*max(1,args.distill_steps))*1e3:.2f} ms per "
+            f"group step; mean loss {h[multi,0].mean():.4g} -> {h[multi,-1].mean():.4g}; layer output error against "
+            f"threshold 1 at threshold 0: parameter mean {rel(before):.4f}, distilled {rel(after):.4f}")
 
     cpu = None
     if not args.no_cpu_baseline:

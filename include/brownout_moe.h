@@ -118,6 +118,27 @@ moe_status moe_build_united(const moe_config *cfg, const moe_ffn_weights *expert
                             float *loss_per_group, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * United-expert distillation (section "United Expert Model"): trains the student of
+ * every group, in place in `united` (bf16, the starting point: moe_build_united's
+ * parameter mean or anything else), to minimise the section's MSE equation
+ *   L^j = (1/k_j) sum_i ||H_u^j - H_o^{j*way+i}||^2
+ * (summed over features, averaged over the n_calib calibration tokens calib_x
+ * [n_calib][d] bf16).  The paper gives no optimiser, settings or data: this call runs
+ * `steps` full-batch steps of Adam (beta1 0.9, beta2 0.999, eps 1e-8, bias corrected,
+ * step size lr) on fp32 master weights; the GEMMs of the forward and backward pass
+ * run in bf16 with fp32 accumulation, teacher outputs are held in half precision.
+ * loss_history (device, [G][steps+1] fp32, may be NULL) receives the loss before every
+ * step and after the last.  A group with one member is not trained: its student becomes
+ * a copy of that member (the minimiser, loss 0).  Workspace: moe_distill_workspace_size bytes.
+ * Errors: n_calib not a positive multiple of 64 (MOE_ERR_SHAPE), NULL pointers,
+ * steps < 0, lr < 0 or NaN, workspace too small.
+ */
+moe_status moe_distill_workspace_size(const moe_config *cfg, int32_t n_calib, size_t *bytes);
+moe_status moe_distill_united(const moe_config *cfg, const moe_ffn_weights *experts, const moe_ffn_weights *united,
+                              const void *calib_x, int32_t n_calib, int32_t steps, float lr, float *loss_history,
+                              void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Gate + TopK + Algorithm 1 + row lists for T tokens x [T][d] bf16.
  *   gate_w [m][d] fp32 (row i = centroid e_i), gate_bias [m] fp32 or NULL:
  *   s_{i,t} = x_t . e_i (+ bias_i), accumulated to fp32 accuracy.

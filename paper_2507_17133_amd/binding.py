@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libbrownout_moe.so")
 MOE_OK = 0
 STAGES = ("prep", "gate", "count", "scan", "scatter", "tiles", "gemm1", "gemm2", "combine")
 EXPORTS = ("moe_status_string", "moe_last_hip_error", "moe_workspace_size", "moe_build_united", "moe_route",
-           "moe_forward", "moe_profile_enable", "moe_profile_collect", "moe_latency_p90", "moe_salc_update")
+           "moe_forward", "moe_distill_workspace_size", "moe_distill_united", "moe_profile_enable", "moe_profile_collect", "moe_latency_p90", "moe_salc_update")
 
 
 class MoeError(RuntimeError):
@@ -67,6 +67,12 @@ def lib():
         L.moe_build_united.restype = C.c_int32
         L.moe_build_united.argtypes = [C.POINTER(moe_config), C.POINTER(moe_ffn_weights), C.POINTER(moe_ffn_weights),
                                        C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.moe_distill_workspace_size.restype = C.c_int32
+        L.moe_distill_workspace_size.argtypes = [C.POINTER(moe_config), C.c_int32, C.POINTER(C.c_size_t)]
+        L.moe_distill_united.restype = C.c_int32
+        L.moe_distill_united.argtypes = [C.POINTER(moe_config), C.POINTER(moe_ffn_weights), C.POINTER(moe_ffn_weights),
+                                         C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p, C.c_size_t,
+                                         C.c_void_p]
         L.moe_route.restype = C.c_int32
         L.moe_route.argtypes = [C.POINTER(moe_config), C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_double,
                                 C.c_int32, C.POINTER(moe_route_out), C.c_void_p, C.c_size_t, C.c_void_p]
@@ -223,6 +229,24 @@ def moe_build_united(cfg: moe_config, experts, calib_x: Optional[torch.Tensor] =
                                   _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream(stream)),
            "moe_build_united")
     return united, loss
+
+
+def moe_distill_united(cfg: moe_config, experts, united, calib_x: torch.Tensor, steps: int, lr: float,
+                       workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Trains `united` in place; returns the loss history [G][steps+1] (fp32, device)."""
+    assert calib_x.is_cuda and calib_x.dtype == torch.bfloat16 and calib_x.is_contiguous()
+    n_calib = calib_x.shape[0]
+    G = (cfg.n_experts + cfg.way - 1) // cfg.way
+    if workspace is None:
+        nbytes = C.c_size_t(0)
+        _check(lib().moe_distill_workspace_size(C.byref(cfg), n_calib, C.byref(nbytes)), "moe_distill_workspace_size")
+        workspace = torch.empty((nbytes.value + 255) // 256 * 256, dtype=torch.uint8, device=calib_x.device)
+    hist = torch.empty((G, steps + 1), dtype=torch.float32, device=calib_x.device)
+    we, wu = _weights(experts), _weights(united)
+    _check(lib().moe_distill_united(C.byref(cfg), C.byref(we), C.byref(wu), _ptr(calib_x), n_calib, steps, lr,
+                                    _ptr(hist), _ptr(workspace), workspace.numel(), _stream(stream)),
+           "moe_distill_united")
+    return hist
 
 
 def profile_enable(stages: Sequence[str] = STAGES):

@@ -402,6 +402,99 @@ moe_status moe_build_united(const moe_config* cfg, const moe_ffn_weights* expert
     return MOE_OK;
 }
 
+static moe_status check_distill(const moe_config* cfg, int32_t n_calib)
+{
+    moe_status st = check_config(cfg);
+    if (st != MOE_OK) return st;
+    if (n_calib <= 0 || n_calib % 64) return MOE_ERR_SHAPE;
+    return check_T(cfg, n_calib);
+}
+
+moe_status moe_distill_workspace_size(const moe_config* cfg, int32_t n_calib, size_t* bytes)
+{
+    if (!bytes) return MOE_ERR_INVALID_ARG;
+    moe_status st = check_distill(cfg, n_calib);
+    if (st != MOE_OK) return st;
+    Dims D = make_dims(*cfg, n_calib);
+    D.ksplit = 1;
+    *bytes = align_up(carve_workspace(D).total, 256) + distill_buffer_bytes(n_calib, D.d, D.F);
+    return MOE_OK;
+}
+
+moe_status moe_distill_united(const moe_config* cfg, const moe_ffn_weights* experts, const moe_ffn_weights* united,
+                              const void* calib_x, int32_t n_calib, int32_t steps, float lr, float* loss_history,
+                              void* workspace, size_t workspace_bytes, void* stream)
+{
+    moe_status st = check_distill(cfg, n_calib);
+    if (st != MOE_OK) return st;
+    st = check_weights(experts);
+    if (st != MOE_OK) return st;
+    st = check_weights(united);
+    if (st != MOE_OK) return st;
+    if (!calib_x || steps < 0 || !(lr >= 0.0f)) return MOE_ERR_INVALID_ARG;
+    if (misaligned(calib_x)) return MOE_ERR_ALIGNMENT;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int m = cfg->n_experts, way = cfg->way, G = ceil_div(m, way);
+    Dims D = make_dims(*cfg, n_calib);
+    D.ksplit = 1;
+    const Workspace W = carve_workspace(D);
+    const size_t fwd_bytes = align_up(W.total, 256);
+    if (!workspace || workspace_bytes < fwd_bytes + distill_buffer_bytes(n_calib, D.d, D.F)) return MOE_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255u) return MOE_ERR_ALIGNMENT;
+    void* buf = static_cast<char*>(workspace) + fwd_bytes;
+    const FfnWeights fe = to_ffn(experts), fu = to_ffn(united), fs{nullptr, nullptr, nullptr};
+    int32_t* unit_cnt = at<int32_t>(workspace, W.unit_cnt);
+    int32_t* unit_off = at<int32_t>(workspace, W.unit_off);
+    float* ones = at<float>(workspace, W.ones);
+    bf16_t* H = at<bf16_t>(workspace, W.H);
+    bf16_t* Yo = at<bf16_t>(workspace, W.Y);
+    int32_t* tiles = at<int32_t>(workspace, W.tiles0);
+    const bf16_t* xb = static_cast<const bf16_t*>(calib_x);
+    const size_t nd = (size_t)n_calib * D.d, dF = (size_t)D.d * D.F;
+    float* tbar = distill_tbar(buf, n_calib, D.d, D.F);
+    float* floor_ = distill_floor(buf, n_calib, D.d, D.F);
+    hipError_t e;
+    auto teacher = [&](int i) -> hipError_t {
+        hipError_t err = launch_single_unit(unit_cnt, unit_off, D.U, i, n_calib, ones, s);
+        if (err != hipSuccess) return err;
+        return launch_ffn(D, i, i + 1, D.F, n_calib, xb, nullptr, unit_cnt, unit_off, fe, fu, fs, tiles, H, Yo, s);
+    };
+    for (int g = 0; g < G; ++g) {
+        const int lo = g * way, hi = lo + way < m ? lo + way : m, k = hi - lo;
+        bf16_t* wu[3] = {static_cast<bf16_t*>(const_cast<void*>(united->w1)) + (size_t)g * dF,
+                         static_cast<bf16_t*>(const_cast<void*>(united->w3)) + (size_t)g * dF,
+                         static_cast<bf16_t*>(const_cast<void*>(united->w2)) + (size_t)g * dF};
+        if (k == 1) {
+            // a lone member is its own best student: the minimiser (loss 0) is known, nothing to train
+            const void* we[3] = {experts->w1, experts->w3, experts->w2};
+            for (int q = 0; q < 3; ++q) {
+                e = hipMemcpyAsync(wu[q], static_cast<const bf16_t*>(we[q]) + (size_t)lo * dF, dF * 2,
+                                   hipMemcpyDeviceToDevice, s);
+                if (e != hipSuccess) return hip_fail(e, "moe_distill_united/copy");
+            }
+            if (loss_history && (e = launch_fill_f32(loss_history + (size_t)g * (steps + 1), steps + 1, 0.0f, s)) != hipSuccess)
+                return hip_fail(e, "moe_distill_united/clear");
+            continue;
+        }
+        if ((e = launch_fill_f32(tbar, nd, 0.0f, s)) != hipSuccess) return hip_fail(e, "moe_distill_united/clear");
+        if ((e = launch_fill_f32(floor_, 1, 0.0f, s)) != hipSuccess) return hip_fail(e, "moe_distill_united/clear");
+        for (int i = lo; i < hi; ++i) {
+            if ((e = teacher(i)) != hipSuccess) return hip_fail(e, "moe_distill_united/teacher");
+            if ((e = launch_teacher_mean(Yo, tbar, nd, 1.0f / (float)k, s)) != hipSuccess)
+                return hip_fail(e, "moe_distill_united/mean");
+        }
+        for (int i = lo; i < hi; ++i) {
+            if ((e = teacher(i)) != hipSuccess) return hip_fail(e, "moe_distill_united/teacher");
+            if ((e = launch_teacher_spread(Yo, tbar, nd, 1.0f / ((float)k * (float)n_calib), floor_, s)) != hipSuccess)
+                return hip_fail(e, "moe_distill_united/spread");
+        }
+        e = distill_group(xb, n_calib, D.d, D.F, wu[0], wu[1], wu[2], steps, lr,
+                          loss_history ? loss_history + (size_t)g * (steps + 1) : nullptr, buf, s);
+        if (e != hipSuccess) return hip_fail(e, "moe_distill_united/train");
+    }
+    return MOE_OK;
+}
+
 moe_status moe_profile_enable(int32_t stage_mask)
 {
     g_prof_mask = (unsigned)stage_mask & ((1u << MOE_N_STAGES) - 1u);

@@ -118,6 +118,7 @@ struct GemmArgs {
     int group_m;                                // M tiles per L2 super-tile
     int ksplit; long plane;                     // GEMM2 only: K split into ksplit slices, slice s writes out + s*plane
     int a_fits_32;                              // every byte offset into A fits 32 bits (gathered A rows)
+    float* out32;                               // plain GEMM only (32- and 64-row kernel): fp32 output instead of out
 };
 
 // Workgroup barrier that orders LDS traffic for the compiler without the vmcnt(0) wait __syncthreads()
@@ -229,7 +230,11 @@ __device__ __forceinline__ void store_tile(const GemmArgs& p, const Tile& t, con
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int col = t.n0 + wn * TN + j * 32 + 8 * q + 4 * (lane >> 5);
-                    if (col < p.N)
+                    if (col >= p.N) continue;
+                    if (p.out32)
+                        *reinterpret_cast<float4*>(p.out32 + (long)(t.row0 + rl) * p.ldo + col) =
+                            make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+                    else
                         *reinterpret_cast<uint2*>(orow + col) =
                             make_uint2(pack_f16(acc[i][j][4 * q], acc[i][j][4 * q + 1]),
                                        pack_f16(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]));
@@ -1137,6 +1142,7 @@ hipError_t launch_ffn(const Dims& D, int u_lo, int u_hi, int Fdim, int64_t expec
     g1.group_m = group_m;
     g1.ksplit = 1; g1.plane = 0;
     g1.a_fits_32 = (uint64_t)D.T * (uint64_t)D.d * 2 < (1ull << 32);
+    g1.out32 = nullptr;
     {
         ProfScope ps(MOE_STAGE_GEMM1, s);
         hipError_t e = dispatch_gemm<true>(BM, g1, max_mtiles, s);
@@ -1152,12 +1158,39 @@ hipError_t launch_ffn(const Dims& D, int u_lo, int u_hi, int Fdim, int64_t expec
     g2.group_m = group_m;
     g2.ksplit = D.ksplit; g2.plane = D.y_plane;
     g2.a_fits_32 = 1;                           // rows of H are addressed relative to the tile
+    g2.out32 = nullptr;
     {
         ProfScope ps(MOE_STAGE_GEMM2, s);
         hipError_t e = dispatch_gemm<false>(BM, g2, max_mtiles, s);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
+}
+
+// ------------------------------------------------------------------------------------------------
+// Plain GEMM for the distillation trainer: C[M][N] (fp32) = A[M][K] . B[N][K]^T, bf16 operands, through
+// the 64-row kernel with a one-unit tile table (table: 4 + 4 * ceil(M/64) ints of scratch).
+// ------------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) plain_table_kernel(int32_t* __restrict__ table, int M)
+{
+    const int n_mt = (M + 63) / 64;
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i == 0) { table[0] = n_mt; table[1] = 0; table[2] = 0; table[3] = 0; }
+    if (i < n_mt) reinterpret_cast<int4*>(table + 4)[i] = make_int4(0, i * 64, min(64, M - i * 64), 0);
+}
+
+hipError_t launch_plain_gemm(const bf16_t* A, const bf16_t* B, int M, int N, int K, float* C, int32_t* table,
+                             hipStream_t s)
+{
+    const int n_mt = ceil_div(M, 64);
+    plain_table_kernel<<<ceil_div(n_mt, 256), 256, 0, s>>>(table, M);
+    GemmArgs g;
+    g.A = A; g.lda = K; g.gather = nullptr; g.table = table;
+    g.wa0 = B; g.wa1 = g.wa2 = nullptr; g.wb0 = g.wb1 = g.wb2 = nullptr;
+    g.m = 1; g.G = 0; g.N = N; g.K = K;
+    g.out = nullptr; g.ldo = N; g.n_ntiles = 0; g.group_m = 4; g.ksplit = 1; g.plane = 0; g.a_fits_32 = 1;
+    g.out32 = C;
+    return launch_small<64, 256, 1, 4, 64, 3, false>(g, n_mt, s);
 }
 
 hipError_t launch_combine(const Dims& D, const bf16_t* x, const bf16_t* Y, const int32_t* token_rows,

@@ -84,6 +84,10 @@ hipError_t launch_combine(const Dims& D, const bf16_t* x, const bf16_t* Y, const
                           const float* row_weight, bf16_t* out, hipStream_t s);
 
 // ---- united experts (united.hip) ----
+// C[M][N] fp32 = A[M][K] . B[N][K]^T (bf16 operands, K a multiple of 64, N a multiple of 64); table: scratch of
+// 4 + 4 * ceil(M/64) ints.
+hipError_t launch_plain_gemm(const bf16_t* A, const bf16_t* B, int M, int N, int K, float* C, int32_t* table,
+                             hipStream_t s);
 hipError_t launch_united_mean(const bf16_t* w, int m, int way, size_t n_elem, bf16_t* u, hipStream_t s);
 hipError_t launch_single_unit(int32_t* unit_cnt, int32_t* unit_off, int U, int u, int n, float* ones,
                               hipStream_t s);
@@ -91,5 +95,16 @@ hipError_t launch_zero_f32(float* p, int n, hipStream_t s);
 // loss[g] += scale * sum_{e<n} (a[e]-b[e])^2   (one block, deterministic)
 hipError_t launch_sqdiff_accumulate(const bf16_t* a, const bf16_t* b, size_t n, float scale, float* loss_g,
                                     hipStream_t s);
+
+// United-expert distillation (distill.hip).  buf: distill_buffer_bytes(n, d, F) bytes of device memory.
+size_t distill_buffer_bytes(int n, int d, int F);
+float* distill_tbar(void* buf, int n, int d, int F);      // [n][d] mean teacher output, filled by the caller
+float* distill_floor(void* buf, int n, int d, int F);     // [1] loss at the mean teacher output
+hipError_t launch_fill_f32(float* p, size_t n, float v, hipStream_t s);
+hipError_t launch_teacher_mean(const bf16_t* y_half, float* tbar, size_t n, float inv_k, hipStream_t s);
+hipError_t launch_teacher_spread(const bf16_t* y_half, const float* tbar, size_t n, float scale, float* floor_,
+                                 hipStream_t s);
+hipError_t distill_group(const bf16_t* x, int n, int d, int F, bf16_t* w1u, bf16_t* w3u, bf16_t* w2u, int steps,
+                         float lr, float* hist, void* buf, hipStream_t s);
 
 }  // namespace bmoe
