@@ -39,9 +39,12 @@ Dims make_dims(const moe_config& c, int T)
     const int64_t tiles2 = (D.row_cap / bm + (D.m + D.G) / 2 + D.Ns) * (int64_t)ceil_div(D.d, 256);
     int ks = 1;
     while (ks < 4 && tiles2 * ks < 1024 && (D.F / 64) / (ks * 2) >= 8) ks *= 2;
+    if (bm == 256) ks = 1;                                // the persistent kernel balances its tail itself
     if (const char* e = std::getenv("BROWNOUT_MOE_KSPLIT")) ks = std::max(1, std::min(8, std::atoi(e)));
     D.ksplit = ks;
     D.y_plane = D.row_cap * (int64_t)D.d;
+    const int64_t max_tiles = (D.row_cap / 256 + D.U) * (int64_t)std::max(ceil_div(D.d, 256), ceil_div(D.Fmax, 128));
+    D.tail_blocks = (int)std::min<int64_t>(kTailBlocks, (max_tiles + 7) / 8 * 8);
     return D;
 }
 
@@ -87,6 +90,13 @@ Workspace carve_workspace(const Dims& D)
     W.H = take((size_t)(W.h_rows + 256) * D.Fmax * 2);
     W.Y = take((size_t)W.y_rows * D.d * 2);
     W.ones = take((size_t)D.T * 4);
+    // K-split tail of the persistent 256-row GEMMs: one fp32 tile per block of their grid
+    W.partial = 0;
+    W.partial_bytes = 0;
+    if (D.ksplit == 1 && pick_tile_rows(D.T) == 256) {
+        W.partial_bytes = (size_t)D.tail_blocks * 256 * 256 * 4;
+        W.partial = take(W.partial_bytes);
+    }
     W.total = o;
     return W;
 }
@@ -316,17 +326,18 @@ moe_status moe_forward(const moe_config* cfg, const void* x, int32_t T, const fl
     const FfnWeights fe = to_ffn(experts), fu = to_ffn(united), fs = to_ffn(shared);
     bf16_t* H = at<bf16_t>(workspace, W.H);
     bf16_t* Y = at<bf16_t>(workspace, W.Y);
+    float* partial = W.partial_bytes ? at<float>(workspace, W.partial) : nullptr;
     const int64_t rows_per_expert = (int64_t)T * D.K / D.m;
     if (D.Ns > 0 && D.Fs != D.F) {
         e = launch_ffn(D, 0, D.m + D.G, D.F, rows_per_expert, xb, R.row_token, R.unit_cnt, R.unit_off,
-                       fe, fu, fs, at<int32_t>(workspace, W.tiles0), H, Y, s);
+                       fe, fu, fs, at<int32_t>(workspace, W.tiles0), H, Y, partial, s);
         if (e != hipSuccess) return hip_fail(e, "moe_forward/ffn");
         e = launch_ffn(D, D.m + D.G, D.U, D.Fs, T, xb, R.row_token, R.unit_cnt, R.unit_off, fe, fu, fs,
-                       at<int32_t>(workspace, W.tiles1), H, Y, s);
+                       at<int32_t>(workspace, W.tiles1), H, Y, partial, s);
         if (e != hipSuccess) return hip_fail(e, "moe_forward/ffn_shared");
     } else {
         e = launch_ffn(D, 0, D.U, D.F, rows_per_expert, xb, R.row_token, R.unit_cnt, R.unit_off, fe, fu,
-                       fs, at<int32_t>(workspace, W.tiles0), H, Y, s);
+                       fs, at<int32_t>(workspace, W.tiles0), H, Y, partial, s);
         if (e != hipSuccess) return hip_fail(e, "moe_forward/ffn");
     }
     e = launch_combine(D, xb, Y, R.token_rows, R.row_weight, static_cast<bf16_t*>(out), s);
@@ -385,7 +396,8 @@ moe_status moe_build_united(const moe_config* cfg, const moe_ffn_weights* expert
     auto run_unit = [&](int u, bf16_t* Y) -> hipError_t {
         hipError_t err = launch_single_unit(unit_cnt, unit_off, D.U, u, n_calib, ones, s);
         if (err != hipSuccess) return err;
-        return launch_ffn(D, u, u + 1, D.F, n_calib, xb, nullptr, unit_cnt, unit_off, fe, fu, fs, tiles, H, Y, s);
+        return launch_ffn(D, u, u + 1, D.F, n_calib, xb, nullptr, unit_cnt, unit_off, fe, fu, fs, tiles, H, Y,
+                          W.partial_bytes ? at<float>(workspace, W.partial) : nullptr, s);
     };
     for (int g = 0; g < G; ++g) {
         const int lo = g * way, hi = lo + way < m ? lo + way : m;
@@ -457,7 +469,8 @@ moe_status moe_distill_united(const moe_config* cfg, const moe_ffn_weights* expe
     auto teacher = [&](int i) -> hipError_t {
         hipError_t err = launch_single_unit(unit_cnt, unit_off, D.U, i, n_calib, ones, s);
         if (err != hipSuccess) return err;
-        return launch_ffn(D, i, i + 1, D.F, n_calib, xb, nullptr, unit_cnt, unit_off, fe, fu, fs, tiles, H, Yo, s);
+        return launch_ffn(D, i, i + 1, D.F, n_calib, xb, nullptr, unit_cnt, unit_off, fe, fu, fs, tiles, H, Yo,
+                          W.partial_bytes ? at<float>(workspace, W.partial) : nullptr, s);
     };
     for (int g = 0; g < G; ++g) {
         const int lo = g * way, hi = lo + way < m ? lo + way : m, k = hi - lo;

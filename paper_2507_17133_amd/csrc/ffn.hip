@@ -119,6 +119,8 @@ struct GemmArgs {
     int ksplit; long plane;                     // GEMM2 only: K split into ksplit slices, slice s writes out + s*plane
     int a_fits_32;                              // every byte offset into A fits 32 bits (gathered A rows)
     float* out32;                               // plain GEMM only (32- and 64-row kernel): fp32 output instead of out
+    float* partial;                             // four-wave kernel, ksplit 1: scratch of the K-split tail (or null)
+    int partial_cap;                            // fp32 tiles it holds
 };
 
 // Workgroup barrier that orders LDS traffic for the compiler without the vmcnt(0) wait __syncthreads()
@@ -137,7 +139,9 @@ __host__ __device__ constexpr int vmcnt_lgkm0_imm(int n) { return vmcnt_imm(n) &
 
 // Which tile a block works on.
 struct Tile {
-    int unit, row0, nrows, nt, n0, kslice;
+    int unit, row0, nrows, nt, n0;
+    int kslice, ks;                             // this block multiplies slice kslice of ks slices of K
+    int part;                                   // slot in GemmArgs::partial the result goes to, or -1: to the output
     const bf16_t *Wa, *Wb;
 };
 
@@ -153,6 +157,8 @@ __device__ __forceinline__ bool decode_tile(const GemmArgs& p, Tile& t)
     const int Lfull = (blockIdx.x & 7) * chunk + bi;           // block id mod 8 = XCD: contiguous range per XCD
     if (Lfull >= total) return false;
     t.kslice = Lfull / tiles;
+    t.ks = p.ksplit;
+    t.part = -1;
     const int L = Lfull - t.kslice * tiles;
     // Super-tiles of group_m M tiles x all N tiles, M fastest: the ~32 blocks an XCD runs at a time
     // cover group_m x (32/group_m) tiles and share their A and B panels in that XCD's L2.
@@ -295,7 +301,7 @@ template <int BK>
 __device__ __forceinline__ void k_range(const GemmArgs& p, const Tile& t, int& k_first, int& nk)
 {
     const int nk_all = p.K / BK;
-    const int nk_per = (nk_all + p.ksplit - 1) / p.ksplit;
+    const int nk_per = (nk_all + t.ks - 1) / t.ks;
     k_first = t.kslice * nk_per;
     nk = max(0, min(nk_all, k_first + nk_per) - k_first);
 }
@@ -705,24 +711,74 @@ __global__ void __launch_bounds__(512) ffn_gemm_rs_kernel(GemmArgs p)
 // Blocks b, b+8, ... share an XCD; block b takes the tiles xcd*chunk + slot, + slots, ... of its XCD's
 // contiguous chunk, so the blocks of an XCD sweep its chunk together.
 // ------------------------------------------------------------------------------------------------
-template <int BNC>
-__device__ __forceinline__ bool decode_tile_at(const GemmArgs& p, int xcd, int bi, Tile& t)
+// K-split tail of the persistent kernel (launches with one plane of output).  With G blocks, the first
+// floor(tiles / G) * G output tiles are whole-tile work, G at a time; the `rem` tiles left over would keep
+// rem of G CUs busy for a whole tile time, so each is cut along K into tail_split() slices, one block each,
+// which write fp32 partial tiles that a small kernel afterwards sums in slice order.  Slices are whole k
+// tiles, at least 8 of them, at most 16 per tile, and none is empty.
+__host__ __device__ inline int tail_split(int G, int rem, int nk_all)
 {
-    const int n_mt = p.table[0];
-    const int tiles = n_mt * p.n_ntiles;
-    const int total = tiles * p.ksplit;
-    const int chunk = (total + 7) >> 3;
-    if (bi >= chunk) return false;
-    const int Lfull = xcd * chunk + bi;
-    if (Lfull >= total) return false;
-    t.kslice = Lfull / tiles;
-    const int L = Lfull - t.kslice * tiles;
+    if (rem <= 0) return 1;
+    int sl = G / rem;
+    sl = sl < 16 ? sl : 16;
+    sl = sl < nk_all / 8 ? sl : nk_all / 8;
+    if (sl <= 1) return 1;
+    const int nk_per = (nk_all + sl - 1) / sl;
+    return (nk_all + nk_per - 1) / nk_per;
+}
+
+// Tile L of the launch's tile order -> its row tile and column tile: super-tiles of group_m M tiles x all N
+// tiles, M fastest.
+__device__ __forceinline__ void tile_coords(const GemmArgs& p, int n_mt, int L, int& mt, int& nt)
+{
     const int gspan = p.group_m * p.n_ntiles;
     const int gi = L / gspan, rem = L - gi * gspan;
     const int mt_first = gi * p.group_m;
     const int gsz = min(p.group_m, n_mt - mt_first);
-    t.nt = rem / gsz;
-    const int mt = mt_first + (rem - t.nt * gsz);
+    nt = rem / gsz;
+    mt = mt_first + (rem - nt * gsz);
+}
+
+template <int BNC, bool TAIL>
+__device__ __forceinline__ bool decode_tile_at(const GemmArgs& p, int xcd, int bi, int slots, Tile& t)
+{
+    const int n_mt = p.table[0];
+    const int tiles = n_mt * p.n_ntiles;
+    int L;
+    t.ks = p.ksplit;
+    t.part = -1;
+    t.kslice = 0;
+    if (!TAIL && p.partial == nullptr) {
+        const int total = tiles * p.ksplit;
+        const int chunk = (total + 7) >> 3;
+        if (bi >= chunk) return false;
+        const int Lfull = xcd * chunk + bi;
+        if (Lfull >= total) return false;
+        t.kslice = Lfull / tiles;
+        L = Lfull - t.kslice * tiles;
+    } else {
+        // Whole tiles: every XCD sweeps its contiguous chunk (a multiple of its `slots` blocks), then one more
+        // round for the tiles left over if they are not split.  A split tail is the work of the TAIL
+        // instantiation, launched next: one slice per block, slice-major, so that the blocks of an XCD work
+        // on the same slices of K.
+        const int G = slots * 8;
+        const int t_full = tiles / G * G, chunk = t_full >> 3;
+        const int rem = tiles - t_full;
+        const int sl = tail_split(G, rem, p.K / 64);
+        if (!TAIL && bi < chunk) {
+            L = xcd * chunk + bi;
+        } else {
+            const int round = TAIL ? bi : bi - chunk;
+            if (round >= slots || (sl > 1) != TAIL) return false;
+            const int c = xcd * slots + round;
+            if (c >= rem * sl) return false;
+            const int pz = c / rem, j = c - pz * rem;
+            L = t_full + j;
+            if (TAIL) { t.kslice = pz; t.ks = sl; t.part = j * sl + pz; }
+        }
+    }
+    int mt;
+    tile_coords(p, n_mt, L, mt, t.nt);
     const int4 te = reinterpret_cast<const int4*>(p.table + 4)[mt];
     t.unit = te.x; t.row0 = te.y; t.nrows = te.z;
     const int src = t.unit < p.m ? 0 : (t.unit < p.m + p.G ? 1 : 2);
@@ -734,7 +790,74 @@ __device__ __forceinline__ bool decode_tile_at(const GemmArgs& p, int xcd, int b
     return true;
 }
 
+// fp32 partial tile of a K slice: 256 x 256 floats, row-major, no masking (the scratch holds whole tiles)
+template <int FM, int FN, int TM, int TN>
+__device__ __forceinline__ void store_partial16(float* __restrict__ dst, const f32x4 (&acc)[FM][FN], int wm, int wn,
+                                                int lane)
+{
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+        float* drow = dst + (wm * TM + i * 16 + (lane & 15)) * 256 + wn * TN + 4 * (lane >> 4);
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+            *reinterpret_cast<float4*>(drow + j * 16) = make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
+    }
+}
+
+// Sums the partial tiles of the K-split tail in slice order and writes the output rows: GEMM2 as they are
+// (half precision), GEMM1 through SwiGLU (bf16; tile columns alternate 16 gate and 16 up columns of the same
+// 16 outputs).  Block = 4 rows of one tail tile, thread = 4 tile columns; G is the grid of the GEMM launch
+// this one follows.
 template <bool SWIGLU>
+__global__ void __launch_bounds__(256) gemm_tail_sum_kernel(GemmArgs p, int G)
+{
+    const int n_mt = p.table[0];
+    const int tiles = n_mt * p.n_ntiles;
+    const int t_full = tiles / G * G, rem = tiles - t_full;
+    const int j = blockIdx.x >> 6, strip = blockIdx.x & 63;
+    if (j >= rem) return;
+    const int sl = tail_split(G, rem, p.K / 64);
+    if (sl <= 1) return;
+    int mt, nt;
+    tile_coords(p, n_mt, t_full + j, mt, nt);
+    const int4 te = reinterpret_cast<const int4*>(p.table + 4)[mt];
+    const int row0 = te.y, nrows = te.z;
+    const int r = strip * 4 + (threadIdx.x >> 6), c = (threadIdx.x & 63) * 4;
+    if (r >= nrows) return;
+    int ocol;                                             // output column of tile column c
+    if (SWIGLU) {
+        if ((c >> 4) & 1) return;                         // up columns are read by the thread of their gate columns
+        ocol = nt * 128 + ((c >> 7) * 4 + ((c & 127) >> 5)) * 16 + (c & 15);
+    } else {
+        ocol = nt * 256 + c;
+    }
+    if (ocol >= p.N) return;
+    const float* src = p.partial + (size_t)j * sl * 65536 + r * 256 + c;
+    constexpr int NV = SWIGLU ? 2 : 1;
+    float4 v[NV][16];                                     // tail_split() yields at most 16 slices
+#pragma unroll
+    for (int pz = 0; pz < 16; ++pz)
+        if (pz < sl) {
+#pragma unroll
+            for (int h = 0; h < NV; ++h) v[h][pz] = *reinterpret_cast<const float4*>(src + (size_t)pz * 65536 + h * 16);
+        }
+    float4 a[NV];
+#pragma unroll
+    for (int h = 0; h < NV; ++h) {
+        a[h] = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int pz = 0; pz < 16; ++pz)
+            if (pz < sl) { a[h].x += v[h][pz].x; a[h].y += v[h][pz].y; a[h].z += v[h][pz].z; a[h].w += v[h][pz].w; }
+    }
+    unsigned short* orow = reinterpret_cast<unsigned short*>(p.out) + (long)(row0 + r) * p.ldo + ocol;
+    if (SWIGLU)
+        *reinterpret_cast<uint2*>(orow) = make_uint2(pack_bf16(swiglu(a[0].x, a[NV - 1].x), swiglu(a[0].y, a[NV - 1].y)),
+                                                     pack_bf16(swiglu(a[0].z, a[NV - 1].z), swiglu(a[0].w, a[NV - 1].w)));
+    else
+        *reinterpret_cast<uint2*>(orow) = make_uint2(pack_f16(a[0].x, a[0].y), pack_f16(a[0].z, a[0].w));
+}
+
+template <bool SWIGLU, bool TAIL>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) ffn_gemm_w4_kernel(GemmArgs p)
 {
     constexpr int BM = 256, BN = 256, BK = 64, NW = 4;
@@ -755,7 +878,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
     const int xcd = blockIdx.x & 7, slots = gridDim.x >> 3;
     int bi = blockIdx.x >> 3;
     Tile t;
-    if (!decode_tile_at<BNC>(p, xcd, bi, t)) return;
+    if (!decode_tile_at<BNC, TAIL>(p, xcd, bi, slots, t)) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);
     const int wm = wave >> 1, wn = wave & 1;
@@ -859,7 +982,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
         // the next output tile of this block, or this one again when there is none (its index load is
         // issued either way, so the number of loads in flight does not depend on it)
         Tile tn;
-        const bool has_next = decode_tile_at<BNC>(p, xcd, bi + slots, tn);
+        const bool has_next = decode_tile_at<BNC, TAIL>(p, xcd, bi + slots, slots, tn);
         if (!has_next) tn = t;
         const int gnext = GATHER ? gather_rows(tn) : 0;
 
@@ -964,7 +1087,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
             // lane-derived epilogue values are recomputed per tile instead of living through the main loop
             int lane_e;
             asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(lane_e));
-            store_tile16<FM, FN, TM, TN, SWIGLU>(p, tcur, acc, wave_s >> 1, wave_s & 1, lane_e);
+            if (TAIL)
+                store_partial16<FM, FN, TM, TN>(p.partial + (size_t)tcur.part * 65536, acc, wave_s >> 1, wave_s & 1, lane_e);
+            else
+                store_tile16<FM, FN, TM, TN, SWIGLU>(p, tcur, acc, wave_s >> 1, wave_s & 1, lane_e);
         }
         if (!has_next) break;
     }
@@ -1083,10 +1209,13 @@ static hipError_t launch_w4(const GemmArgs& a, int max_mtiles, hipStream_t s)
     constexpr int LDS = 160 * 1024;
     static bool attr_set = false;
     static int n_cu = 0;
-    auto kern = ffn_gemm_w4_kernel<SWIGLU>;
+    auto kern = ffn_gemm_w4_kernel<SWIGLU, false>;
+    auto kern_tail = ffn_gemm_w4_kernel<SWIGLU, true>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern_tail), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
         if (e != hipSuccess) return e;
         int dev = 0;
         e = hipGetDevice(&dev);
@@ -1101,7 +1230,17 @@ static hipError_t launch_w4(const GemmArgs& a, int max_mtiles, hipStream_t s)
     // one block per CU (the LDS footprint allows no second one), a multiple of 8 so every XCD has the same
     // number of blocks; fewer when there cannot be that many tiles
     const int grid = (int)std::min<long>((total + 7) / 8 * 8, std::max(8, n_cu / 8 * 8));
+    if (g.ksplit != 1 || grid > g.partial_cap) g.partial = nullptr;
     kern<<<grid, 256, LDS, s>>>(g);
+    if (g.partial) {
+        // the tiles left over after the last full round of `grid` tiles, cut along K (one slice per block),
+        // then summed; which of the two it is, if any, only the tile table on the device knows
+        const int max_tail = (int)std::min<long>(total, grid - 1);
+        if (max_tail > 0) {
+            kern_tail<<<grid, 256, LDS, s>>>(g);
+            gemm_tail_sum_kernel<SWIGLU><<<max_tail * 64, 256, 0, s>>>(g, grid);
+        }
+    }
     return hipGetLastError();
 }
 
@@ -1121,7 +1260,7 @@ static hipError_t dispatch_gemm(int BM, const GemmArgs& a, int max_mtiles, hipSt
 hipError_t launch_ffn(const Dims& D, int u_lo, int u_hi, int Fdim, int64_t expected_rows, const bf16_t* x,
                       const int32_t* gather, const int32_t* unit_cnt, const int32_t* unit_off,
                       const FfnWeights& experts, const FfnWeights& united,
-                      const FfnWeights& shared, int32_t* tile_table, bf16_t* H, bf16_t* Y, hipStream_t s)
+                      const FfnWeights& shared, int32_t* tile_table, bf16_t* H, bf16_t* Y, float* partial, hipStream_t s)
 {
     const int n_units = u_hi - u_lo;
     const int BM = pick_tile_rows(expected_rows);
@@ -1142,7 +1281,7 @@ hipError_t launch_ffn(const Dims& D, int u_lo, int u_hi, int Fdim, int64_t expec
     g1.group_m = group_m;
     g1.ksplit = 1; g1.plane = 0;
     g1.a_fits_32 = (uint64_t)D.T * (uint64_t)D.d * 2 < (1ull << 32);
-    g1.out32 = nullptr;
+    g1.out32 = nullptr; g1.partial = partial; g1.partial_cap = D.tail_blocks;
     {
         ProfScope ps(MOE_STAGE_GEMM1, s);
         hipError_t e = dispatch_gemm<true>(BM, g1, max_mtiles, s);
@@ -1158,7 +1297,7 @@ hipError_t launch_ffn(const Dims& D, int u_lo, int u_hi, int Fdim, int64_t expec
     g2.group_m = group_m;
     g2.ksplit = D.ksplit; g2.plane = D.y_plane;
     g2.a_fits_32 = 1;                           // rows of H are addressed relative to the tile
-    g2.out32 = nullptr;
+    g2.out32 = nullptr; g2.partial = partial; g2.partial_cap = D.tail_blocks;
     {
         ProfScope ps(MOE_STAGE_GEMM2, s);
         hipError_t e = dispatch_gemm<false>(BM, g2, max_mtiles, s);
@@ -1189,7 +1328,7 @@ hipError_t launch_plain_gemm(const bf16_t* A, const bf16_t* B, int M, int N, int
     g.wa0 = B; g.wa1 = g.wa2 = nullptr; g.wb0 = g.wb1 = g.wb2 = nullptr;
     g.m = 1; g.G = 0; g.N = N; g.K = K;
     g.out = nullptr; g.ldo = N; g.n_ntiles = 0; g.group_m = 4; g.ksplit = 1; g.plane = 0; g.a_fits_32 = 1;
-    g.out32 = C;
+    g.out32 = C; g.partial = nullptr; g.partial_cap = 0;
     return launch_small<64, 256, 1, 4, 64, 3, false>(g, n_mt, s);
 }
 

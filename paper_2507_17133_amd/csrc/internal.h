@@ -17,6 +17,7 @@ constexpr int kMaxShared = 8;     // N_s
 constexpr int kMaxUnits = kMaxExperts + kMaxExperts + kMaxShared;  // U
 constexpr int kSegTokens = 64;    // tokens per routing segment (one wavefront)
 constexpr int kMinTileRows = 32;  // smallest GEMM M tile
+constexpr int kTailBlocks = 256;  // largest grid of the persistent GEMM whose K-split tail has scratch (one block per CU)
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -30,6 +31,7 @@ struct Dims {
     int tile_cap;      // entries of one GEMM tile table
     int ksplit;        // K slices of GEMM2 (partial products in separate planes of Y)
     int64_t y_plane;   // elements between two planes of Y
+    int tail_blocks;   // fp32 tiles in the scratch of the persistent GEMM's K-split tail (a bound on its grid)
 };
 Dims make_dims(const moe_config& c, int T);
 // GEMM tile height from the expected rows per expert (the real counts stay on the device).
@@ -45,6 +47,7 @@ struct Workspace {
     size_t H;                                         // [h_rows][Fmax] bf16
     size_t Y;                                         // [y_rows][d], IEEE half (2 bytes; carried as bf16_t*)
     size_t ones;                                      // [T] fp32 (build_united)
+    size_t partial, partial_bytes;                    // fp32 tiles of GEMM2's K-split tail (256-row tiles, one plane)
     size_t total;
     int64_t h_rows, y_rows;
 };
@@ -79,7 +82,7 @@ struct FfnWeights { const bf16_t *w1, *w3, *w2; };
 hipError_t launch_ffn(const Dims& D, int u_lo, int u_hi, int Fdim, int64_t expected_rows, const bf16_t* x,
                       const int32_t* gather, const int32_t* unit_cnt, const int32_t* unit_off,
                       const FfnWeights& experts, const FfnWeights& united,
-                      const FfnWeights& shared, int32_t* tile_table, bf16_t* H, bf16_t* Y, hipStream_t s);
+                      const FfnWeights& shared, int32_t* tile_table, bf16_t* H, bf16_t* Y, float* partial, hipStream_t s);
 hipError_t launch_combine(const Dims& D, const bf16_t* x, const bf16_t* Y, const int32_t* token_rows,
                           const float* row_weight, bf16_t* out, hipStream_t s);
 
