@@ -135,7 +135,8 @@ def main():
         achieved = flops_gemm1 / (gemm1_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None}
-    roofline["kernel"] = "GEMM1 (ffn_gemm_*_kernel<SWIGLU>)"
+    # with 256-row tiles GEMM1 is three launches (the GEMM kernel, its K-split tail, the tail sum): all timed
+    roofline["kernel"] = "GEMM1 (ffn_gemm_*_kernel<SWIGLU> and, with 256-row tiles, its K-split tail)"
     roofline["kernel_ms"] = gemm1_ms
     # HBM bytes of one GEMM1 launch as counted by rocprofv3 (FETCH_SIZE + WRITE_SIZE, scaled by a copy
     # probe): taken from the committed profile summary of this workload, if there is one
@@ -143,7 +144,7 @@ def main():
     if os.path.exists(tpath) and args.fraction is None and args.way is None and args.tokens is None:
         for ln in open(tpath):
             if ln.startswith("gemm1_hbm_bytes_per_launch"):
-                roofline["traffic"] = float(ln.split("=")[1])
+                roofline["traffic"] = float(ln.split("=")[1].split()[0])
     log(f"  step {ms_per_step:.3f} ms  -> {tokens_per_s/1e6:.3f} M tok/s; layer roofline time "
         f"{max(t_mfma, t_hbm)*1e3:.3f} ms ({'HBM' if hbm_bound else 'MFMA'}-bound) -> whole-step fraction "
         f"{max(t_mfma, t_hbm)*1e3/ms_per_step:.3f}; GEMM1 {gemm1_ms:.3f} ms")

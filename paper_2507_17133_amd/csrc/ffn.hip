@@ -715,7 +715,7 @@ __global__ void __launch_bounds__(512) ffn_gemm_rs_kernel(GemmArgs p)
 // floor(tiles / G) * G output tiles are whole-tile work, G at a time; the `rem` tiles left over would keep
 // rem of G CUs busy for a whole tile time, so each is cut along K into tail_split() slices, one block each,
 // which write fp32 partial tiles that a small kernel afterwards sums in slice order.  Slices are whole k
-// tiles, at least 8 of them, at most 16 per tile, and none is empty.
+// tiles, at least 8 of them, at most 16 per tile, and none is empty; no split when it would not pay.
 __host__ __device__ inline int tail_split(int G, int rem, int nk_all)
 {
     if (rem <= 0) return 1;
@@ -724,7 +724,10 @@ __host__ __device__ inline int tail_split(int G, int rem, int nk_all)
     sl = sl < nk_all / 8 ? sl : nk_all / 8;
     if (sl <= 1) return 1;
     const int nk_per = (nk_all + sl - 1) / sl;
-    return (nk_all + nk_per - 1) / nk_per;
+    sl = (nk_all + nk_per - 1) / nk_per;
+    // Worth it?  In units of one k tile's time (about 1.4 us): a whole tile costs nk_all + 5, the tail saves
+    // (1 - 1/sl) of that, and costs about 7 for its launches plus 1/8 per partial tile written and read back.
+    return (nk_all + 5) * (sl - 1) > sl * (rem * sl / 8 + 7) ? sl : 1;
 }
 
 // Tile L of the launch's tile order -> its row tile and column tile: super-tiles of group_m M tiles x all N

@@ -59,13 +59,26 @@ __global__ void __launch_bounds__(256) prep_kernel(const float* __restrict__ gat
 // ------------------------------------------------------------------------------------------------
 struct GateArgs {
     const bf16_t* x; const unsigned short* split; const float* bias;
-    int T, d, m, m_pad, K, score_fn, NG, KS;
+    int T, d, m, m_pad, K, score_fn, NG, KS, n_stage;
     int32_t* topk_idx; float* topk_w; int32_t* expert_cnt; uint8_t* near_tie;
 };
 
 // TopK(.,K) of one token by one wavefront: lane holds experts lane, lane+64, ...; K (+1 for the best
 // loser) rounds of "best of my candidates, then best across lanes" (higher score, equal scores: lower
 // id); lane j keeps the j-th winner, weights are normalised over lanes 0..K-1.
+// row_ror:n of a 16-lane row (DPP control 0x120 + n): lane l reads lane (l - n) mod 16 of its row
+template <int CTRL>
+__device__ __forceinline__ int dpp_i(int v) { return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, false); }
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) { return __int_as_float(dpp_i<CTRL>(__float_as_int(v))); }
+
+// (bv, bi) <- the better of it and (ov, oi): higher score, equal scores: lower id; id 0x7fffffff = none
+__device__ __forceinline__ void better(float& bv, int& bi, float ov, int oi)
+{
+    const bool take = oi != 0x7fffffff && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi));
+    if (take) { bv = ov; bi = oi; }
+}
+
 __device__ __forceinline__ void topk_token(const GateArgs& p, const float* logit_row, int t, int lane, int* hist)
 {
     const int K = p.K;
@@ -88,15 +101,26 @@ __device__ __forceinline__ void topk_token(const GateArgs& p, const float* logit
             if (taken & (1u << c)) continue;
             if (bi == 0x7fffffff || v[c] > bv) { bv = v[c]; bi = lane + 64 * c; }
         }
+        // best of the wavefront: inside each row of 16 lanes by rotations (data-parallel primitives, no trip
+        // through the LDS crossbar; "better" is idempotent, so four rotations leave the row's best in every
+        // lane), then across the four rows through scalar registers
+        better(bv, bi, dpp_f<0x121>(bv), dpp_i<0x121>(bi));
+        better(bv, bi, dpp_f<0x122>(bv), dpp_i<0x122>(bi));
+        better(bv, bi, dpp_f<0x124>(bv), dpp_i<0x124>(bi));
+        better(bv, bi, dpp_f<0x128>(bv), dpp_i<0x128>(bi));
+        {
+            float rv[4];
+            int ri[4];
 #pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) {
-            const float ov = __shfl_xor(bv, off);
-            const int oi = __shfl_xor(bi, off);
-            const bool take = oi != 0x7fffffff && (bi == 0x7fffffff || ov > bv || (ov == bv && oi < bi));
-            if (take) { bv = ov; bi = oi; }
+            for (int q = 0; q < 4; ++q) {
+                rv[q] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(bv), 16 * q));
+                ri[q] = __builtin_amdgcn_readlane(bi, 16 * q);
+            }
+            bv = rv[0];
+            bi = ri[0];
+#pragma unroll
+            for (int q = 1; q < 4; ++q) better(bv, bi, rv[q], ri[q]);
         }
-        bv = __shfl(bv, 0);
-        bi = __shfl(bi, 0);
         if ((bi & 63) == lane) taken |= 1u << (bi >> 6);
         if (lane == j) { my_v = bv; my_i = bi; }
     }
@@ -245,10 +269,31 @@ __global__ void __launch_bounds__(1024) gate_topk_kernel(GateArgs p)
 // together with the block's x rows and read by every wave, so the split gate matrix is fetched once per
 // 16*TG tokens instead of once per 16.  Same arithmetic as gate_topk_kernel.
 // ------------------------------------------------------------------------------------------------
+// s_waitcnt vmcnt(n) for a run-time n (the instruction takes an immediate): waits for at most the largest
+// listed value <= n, which is never too lax.
+__device__ __forceinline__ void wait_vmcnt_at_most(int n)
+{
+    if (n >= 48) __builtin_amdgcn_s_waitcnt(0xCF70);        // vmcnt 48: low four bits 0, bits 15:14 = 3
+    else if (n >= 32) __builtin_amdgcn_s_waitcnt(0x8F70);
+    else if (n >= 24) __builtin_amdgcn_s_waitcnt(0x4F78);
+    else if (n >= 20) __builtin_amdgcn_s_waitcnt(0x4F74);
+    else if (n >= 16) __builtin_amdgcn_s_waitcnt(0x4F70);
+    else if (n >= 12) __builtin_amdgcn_s_waitcnt(0x0F7C);
+    else if (n >= 9) __builtin_amdgcn_s_waitcnt(0x0F79);
+    else if (n >= 8) __builtin_amdgcn_s_waitcnt(0x0F78);
+    else if (n >= 6) __builtin_amdgcn_s_waitcnt(0x0F76);
+    else if (n >= 4) __builtin_amdgcn_s_waitcnt(0x0F74);
+    else if (n >= 3) __builtin_amdgcn_s_waitcnt(0x0F73);
+    else if (n >= 2) __builtin_amdgcn_s_waitcnt(0x0F72);
+    else if (n >= 1) __builtin_amdgcn_s_waitcnt(0x0F71);
+    else __builtin_amdgcn_s_waitcnt(0x0F70);
+}
+
 template <int TG, int NTH>
 __global__ void __launch_bounds__(TG * 128) gate_tiled_kernel(GateArgs p)
 {
-    constexpr int NWV = 2 * TG, NST = 3;
+    constexpr int NWV = 2 * TG;
+    const int NST = p.n_stage;                          // LDS stages: as many as fit, at most 8
     extern __shared__ __attribute__((aligned(16))) char gsm[];
     __shared__ int hist[kMaxExperts];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -264,17 +309,26 @@ __global__ void __launch_bounds__(TG * 128) gate_tiled_kernel(GateArgs p)
     // loader: wave w moves row groups w, w+NWV, ...; lane -> row lane/4, 16-byte slot lane%4 holding
     // chunk (lane%4) ^ ((row/4)&3)  (conflict-free ds_read_b128 on the 64-bank LDS)
     const int ksteps = p.d >> 5;
-    auto issue = [&](int ks) {
-        char* dst = gsm + (ks % NST) * stage_bytes;
-        for (int g = wave; g < groups; g += NWV) {
-            const int row = g * 16 + (lane >> 2);
-            const int chunk = (lane & 3) ^ ((row >> 2) & 3);
-            const unsigned short* src;
-            if (row < w_rows) src = p.split + (size_t)row * p.d;
-            else src = reinterpret_cast<const unsigned short*>(p.x) + (size_t)min(t0 + row - w_rows, p.T - 1) * p.d;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + (ks << 5) + chunk * 8),
-                                             (__attribute__((address_space(3))) void*)(dst + g * 1024), 16, 0, 0);
-        }
+    // the source address of every load of a stage is fixed up to the k offset: computed once, not per step
+    constexpr int MAXS = (3 * kMaxExperts + 16 * TG + 16 * NWV - 1) / (16 * NWV);
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+    const unsigned short* srcp[MAXS];
+#pragma unroll
+    for (int i = 0; i < MAXS; ++i) {
+        const int row = min((wave + i * NWV) * 16 + (lane >> 2), rows - 1);
+        const int chunk = (lane & 3) ^ ((row >> 2) & 3);
+        const unsigned short* src;
+        if (row < w_rows) src = p.split + (size_t)row * p.d;
+        else src = reinterpret_cast<const unsigned short*>(p.x) + (size_t)min(t0 + row - w_rows, p.T - 1) * p.d;
+        srcp[i] = src + chunk * 8;
+    }
+    auto issue = [&](int ks, int buf) {
+        char* dst = gsm + buf * stage_bytes + wave_s * 1024;
+#pragma unroll
+        for (int i = 0; i < MAXS; ++i)
+            if (wave_s + i * NWV < groups)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(srcp[i] + (ks << 5)),
+                                                 (__attribute__((address_space(3))) void*)(dst + i * NWV * 1024), 16, 0, 0);
     };
 
     double sum[NTH][4];
@@ -294,32 +348,35 @@ __global__ void __launch_bounds__(TG * 128) gate_tiled_kernel(GateArgs p)
     const int arow = w_rows + tg * 16 + (lane & 15);
     const int aoff = arow * 64 + (((lane >> 4) ^ ((arow >> 2) & 3)) << 4);
     // All loads of the loop go to LDS and complete in order per wave: at the top of step ks the loads of
-    // stage ks are older than the `young` loads of stage ks+1, which may stay in flight.
+    // stage ks are older than those of the later stages, which may stay in flight.  A step is little work
+    // (a dozen MFMAs per wave), so the depth of this queue, not the arithmetic, sets the pace.
     const int young = groups / NWV;                     // loads of one stage every wave issues at least
-    issue(0);
-    if (ksteps > 1) issue(1);
+    for (int q = 0; q < NST - 1; ++q)
+        if (q < ksteps) issue(q, q);
+    int buf = 0, buf_ld = NST - 1;                      // stage read at step ks = ks mod NST; stage refilled = (ks-1) mod NST
     for (int ks = 0; ks < ksteps; ++ks) {
-        if (ks + 1 >= ksteps) __builtin_amdgcn_s_waitcnt(0x0F70);
-        else if (young >= 6) __builtin_amdgcn_s_waitcnt(0x0F76);
-        else if (young >= 3) __builtin_amdgcn_s_waitcnt(0x0F73);
-        else if (young >= 2) __builtin_amdgcn_s_waitcnt(0x0F72);
-        else if (young >= 1) __builtin_amdgcn_s_waitcnt(0x0F71);
-        else __builtin_amdgcn_s_waitcnt(0x0F70);
+        // stages ks+1 .. ks+NST-2 (those that exist) may stay in flight: at least `young` loads each
+        wait_vmcnt_at_most(min(NST - 2, ksteps - 1 - ks) * young);
         asm volatile("" ::: "memory");
         __builtin_amdgcn_s_barrier();                   // stage ks is in LDS for everyone; stage ks-1 is free
         asm volatile("" ::: "memory");
-        if (ks + 2 < ksteps) issue(ks + 2);
-        const char* St = gsm + (ks % NST) * stage_bytes;
+        if (ks + NST - 1 < ksteps) issue(ks + NST - 1, buf_ld);
+        const char* St = gsm + buf * stage_bytes;
+        buf_ld = buf;
+        buf = buf + 1 == NST ? 0 : buf + 1;
         const bf16x8 a = *reinterpret_cast<const bf16x8*>(St + aoff);
+        // low piece first in every expert tile (the sum of a tile is taken in that order); piece by piece
+        // across the tiles, so that consecutive MFMAs do not wait for each other's result
+        bf16x8 b[3][NTH];
 #pragma unroll
-        for (int nt = 0; nt < NTH; ++nt) {
-            const bf16x8 b_hi = *reinterpret_cast<const bf16x8*>(St + boff[nt]);
-            const bf16x8 b_mid = *reinterpret_cast<const bf16x8*>(St + p.m_pad * 64 + boff[nt]);
-            const bf16x8 b_lo = *reinterpret_cast<const bf16x8*>(St + 2 * p.m_pad * 64 + boff[nt]);
-            acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_lo, acc[nt], 0, 0, 0);
-            acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_mid, acc[nt], 0, 0, 0);
-            acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_hi, acc[nt], 0, 0, 0);
-        }
+        for (int pz = 0; pz < 3; ++pz)
+#pragma unroll
+            for (int nt = 0; nt < NTH; ++nt)
+                b[pz][nt] = *reinterpret_cast<const bf16x8*>(St + pz * p.m_pad * 64 + boff[nt]);
+#pragma unroll
+        for (int pz = 2; pz >= 0; --pz)
+#pragma unroll
+            for (int nt = 0; nt < NTH; ++nt) acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b[pz][nt], acc[nt], 0, 0, 0);
         if ((ks & 1) == 1 || ks + 1 == ksteps) {
 #pragma unroll
             for (int nt = 0; nt < NTH; ++nt) {
@@ -610,6 +667,8 @@ __global__ void __launch_bounds__(1024) route_small_kernel(RowArgs p)
     if (t < p.T) scatter_token(p, unit_s, bm + (size_t)wave * p.U, off_s, segoff + wave * p.U, t, lane);
 }
 
+constexpr int kGateLds = 160 * 1024;                    // LDS of one CU (the tiled gate also holds a 1 KiB histogram)
+
 hipError_t launch_route(const Dims& D, const bf16_t* x, const float* gate_w, const float* gate_bias,
                         double threshold, int full_brownout, const RouteBufs& R, bf16_t* gate_split,
                         int32_t* seg_cnt, int32_t* seg_off, hipStream_t s)
@@ -625,7 +684,7 @@ hipError_t launch_route(const Dims& D, const bf16_t* x, const float* gate_w, con
         ProfScope ps(MOE_STAGE_GATE, s);
         GateArgs g;
         g.x = x; g.split = reinterpret_cast<const unsigned short*>(gate_split); g.bias = gate_bias;
-        g.T = D.T; g.d = D.d; g.m = D.m; g.m_pad = D.m_pad; g.K = D.K; g.score_fn = D.score_fn;
+        g.T = D.T; g.d = D.d; g.m = D.m; g.m_pad = D.m_pad; g.K = D.K; g.score_fn = D.score_fn; g.n_stage = 3;
         const int n_tiles = D.m_pad / 16;
         g.NG = n_tiles < 4 ? n_tiles : 4;
         g.KS = std::max(1, std::min(16 / g.NG, 256 / D.m_pad));
@@ -635,7 +694,9 @@ hipError_t launch_route(const Dims& D, const bf16_t* x, const float* gate_w, con
         const int half_tiles = ceil_div(n_tiles, 2);
         const int tgw = D.T >= 64 * 192 ? 4 : (D.T >= 32 * 192 ? 2 : 0);
         if (n_tiles >= 4 && tgw != 0) {
-            const int lds = std::max(3 * (3 * D.m_pad + 16 * tgw) * 64, 16 * tgw * D.m_pad * 4);
+            const int stage = (3 * D.m_pad + 16 * tgw) * 64;
+            g.n_stage = std::max(3, std::min(8, (kGateLds - 1024) / stage));
+            const int lds = std::max(g.n_stage * stage, 16 * tgw * D.m_pad * 4);
             const int blocks = ceil_div(D.T, 16 * tgw);
             hipError_t e = hipSuccess;
 #define BMOE_GATE_TILED(TG_, NTH_)                                                                               \
@@ -644,7 +705,7 @@ hipError_t launch_route(const Dims& D, const bf16_t* x, const float* gate_w, con
                 if (!attr_set) {                                                                                   \
                     e = hipFuncSetAttribute(reinterpret_cast<const void*>(gate_tiled_kernel<TG_, NTH_>),           \
                                             hipFuncAttributeMaxDynamicSharedMemorySize,                            \
-                                            3 * (3 * kMaxExperts + 16 * TG_) * 64);                                \
+                                            kGateLds - 1024);                                                      \
                     attr_set = e == hipSuccess;                                                                    \
                 }                                                                                                  \
                 if (e == hipSuccess) gate_tiled_kernel<TG_, NTH_><<<blocks, TG_ * 128, lds, s>>>(g);               \

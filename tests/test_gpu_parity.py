@@ -48,12 +48,13 @@ SMALL = {
     "mid_tile": (WL.LayerConfig("mid_tile", T=600, d=128, F=256, m=8, K=2, way=4), [1.0, 0.5]),
     "multi_tile": (WL.LayerConfig("multi_tile", T=1500, d=256, F=384, m=4, K=2, way=4, zipf_s=1.2), [1.0, 0.7]),
     # 256-row tiles with long K: the persistent GEMM cuts the tiles left over after its last full round of one
-    # tile per block along K (here: fewer tiles than blocks, every tile is cut; ragged last tile)
-    "k_split_tail_few_tiles": (WL.LayerConfig("k_split_tail_few", T=500, d=1024, F=4096, m=2, K=2, way=2),
-                               [0.0, 1.0]),
-    # ... and more tiles than blocks: whole tiles first, then the cut remainder
-    "k_split_tail_after_full_rounds": (WL.LayerConfig("k_split_tail_full", T=2200, d=1024, F=4096, m=2, K=2, way=2),
-                                       [0.0]),
+    # tile per block along K.  Fewer tiles than blocks, ragged last tile: GEMM2 cut four ways ...
+    "k_split_tail_gemm2": (WL.LayerConfig("k_split_tail_gemm2", T=500, d=1024, F=4096, m=2, K=2, way=2), [0.0, 1.0]),
+    # ... GEMM1 cut three ways (SwiGLU applied to the summed slices) ...
+    "k_split_tail_gemm1": (WL.LayerConfig("k_split_tail_gemm1", T=500, d=4096, F=512, m=2, K=2, way=2), [0.0]),
+    # ... and more tiles than blocks in GEMM1: one round of whole tiles, then the remainder cut eight ways
+    "k_split_tail_after_full_round": (WL.LayerConfig("k_split_tail_full", T=2200, d=4096, F=4096, m=2, K=2, way=2),
+                                      [0.0]),
     # the largest K and number of shared experts the library accepts
     "max_topk_max_shared": (WL.LayerConfig("max_topk_max_shared", T=48, d=64, F=64, m=64, K=32, way=8, n_shared=8,
                                            F_s=64), [1.0, 0.5]),
