@@ -115,7 +115,8 @@ def main():
     ms_per_step = (t2 - t1) * 1e3 / args.steps
     tokens_per_s = cfg.T * args.steps / (t2 - t1)
 
-    gemm1_ms = prof["gemm1"][0] / max(1, prof["gemm1"][1])
+    # GEMM1 time per step (a layer whose shared experts have their own width runs GEMM1 twice per step)
+    gemm1_ms = prof["gemm1"][0] / args.steps
     # algorithmic flops of GEMM1 per launch: rows x (W1 and W3) : 2*2*d*F per row (shared rows with their own F)
     flops_gemm1 = 4.0 * cfg.d * (cfg.F * n_routed_rows + cfg.F_s * n_shared_rows)
     flops_step = 6.0 * cfg.d * (cfg.F * n_routed_rows + cfg.F_s * n_shared_rows) + 2.0 * cfg.T * cfg.d * cfg.m
