@@ -809,55 +809,54 @@ __device__ __forceinline__ void store_partial16(float* __restrict__ dst, const f
 
 // Sums the partial tiles of the K-split tail in slice order and writes the output rows: GEMM2 as they are
 // (half precision), GEMM1 through SwiGLU (bf16; tile columns alternate 16 gate and 16 up columns of the same
-// 16 outputs).  Block = 4 rows of one tail tile, thread = 4 tile columns; G is the grid of the GEMM launch
-// this one follows.
+// 16 outputs).  A block handles 4 rows of one tail tile at a time, a thread 4 tile columns; G is the grid of
+// the GEMM launch this one follows.
 template <bool SWIGLU>
 __global__ void __launch_bounds__(256) gemm_tail_sum_kernel(GemmArgs p, int G)
 {
     const int n_mt = p.table[0];
     const int tiles = n_mt * p.n_ntiles;
     const int t_full = tiles / G * G, rem = tiles - t_full;
-    const int j = blockIdx.x >> 6, strip = blockIdx.x & 63;
-    if (j >= rem) return;
     const int sl = tail_split(G, rem, p.K / 64);
     if (sl <= 1) return;
-    int mt, nt;
-    tile_coords(p, n_mt, t_full + j, mt, nt);
-    const int4 te = reinterpret_cast<const int4*>(p.table + 4)[mt];
-    const int row0 = te.y, nrows = te.z;
-    const int r = strip * 4 + (threadIdx.x >> 6), c = (threadIdx.x & 63) * 4;
-    if (r >= nrows) return;
-    int ocol;                                             // output column of tile column c
-    if (SWIGLU) {
-        if ((c >> 4) & 1) return;                         // up columns are read by the thread of their gate columns
-        ocol = nt * 128 + ((c >> 7) * 4 + ((c & 127) >> 5)) * 16 + (c & 15);
-    } else {
-        ocol = nt * 256 + c;
-    }
-    if (ocol >= p.N) return;
-    const float* src = p.partial + (size_t)j * sl * 65536 + r * 256 + c;
-    constexpr int NV = SWIGLU ? 2 : 1;
-    float4 v[NV][16];                                     // tail_split() yields at most 16 slices
-#pragma unroll
-    for (int pz = 0; pz < 16; ++pz)
-        if (pz < sl) {
-#pragma unroll
-            for (int h = 0; h < NV; ++h) v[h][pz] = *reinterpret_cast<const float4*>(src + (size_t)pz * 65536 + h * 16);
-        }
-    float4 a[NV];
-#pragma unroll
-    for (int h = 0; h < NV; ++h) {
-        a[h] = make_float4(0.f, 0.f, 0.f, 0.f);
+    const int c = (threadIdx.x & 63) * 4;
+    if (SWIGLU && ((c >> 4) & 1)) return;                 // up columns are read by the thread of their gate columns
+    // how many tiles are left over only the device knows: a fixed grid strides over (tile, 4-row strip)
+    for (int item = blockIdx.x; item < rem * 64; item += gridDim.x) {
+        const int j = item >> 6, strip = item & 63;
+        int mt, nt;
+        tile_coords(p, n_mt, t_full + j, mt, nt);
+        const int4 te = reinterpret_cast<const int4*>(p.table + 4)[mt];
+        const int row0 = te.y, nrows = te.z;
+        const int r = strip * 4 + (threadIdx.x >> 6);
+        if (r >= nrows) continue;
+        // output column of tile column c
+        const int ocol = SWIGLU ? nt * 128 + ((c >> 7) * 4 + ((c & 127) >> 5)) * 16 + (c & 15) : nt * 256 + c;
+        if (ocol >= p.N) continue;
+        const float* src = p.partial + (size_t)j * sl * 65536 + r * 256 + c;
+        constexpr int NV = SWIGLU ? 2 : 1;
+        float4 v[NV][16];                                     // tail_split() yields at most 16 slices
 #pragma unroll
         for (int pz = 0; pz < 16; ++pz)
-            if (pz < sl) { a[h].x += v[h][pz].x; a[h].y += v[h][pz].y; a[h].z += v[h][pz].z; a[h].w += v[h][pz].w; }
+            if (pz < sl) {
+#pragma unroll
+                for (int h = 0; h < NV; ++h) v[h][pz] = *reinterpret_cast<const float4*>(src + (size_t)pz * 65536 + h * 16);
+            }
+        float4 a[NV];
+#pragma unroll
+        for (int h = 0; h < NV; ++h) {
+            a[h] = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int pz = 0; pz < 16; ++pz)
+                if (pz < sl) { a[h].x += v[h][pz].x; a[h].y += v[h][pz].y; a[h].z += v[h][pz].z; a[h].w += v[h][pz].w; }
+        }
+        unsigned short* orow = reinterpret_cast<unsigned short*>(p.out) + (long)(row0 + r) * p.ldo + ocol;
+        if (SWIGLU)
+            *reinterpret_cast<uint2*>(orow) = make_uint2(pack_bf16(swiglu(a[0].x, a[NV - 1].x), swiglu(a[0].y, a[NV - 1].y)),
+                                                         pack_bf16(swiglu(a[0].z, a[NV - 1].z), swiglu(a[0].w, a[NV - 1].w)));
+        else
+            *reinterpret_cast<uint2*>(orow) = make_uint2(pack_f16(a[0].x, a[0].y), pack_f16(a[0].z, a[0].w));
     }
-    unsigned short* orow = reinterpret_cast<unsigned short*>(p.out) + (long)(row0 + r) * p.ldo + ocol;
-    if (SWIGLU)
-        *reinterpret_cast<uint2*>(orow) = make_uint2(pack_bf16(swiglu(a[0].x, a[NV - 1].x), swiglu(a[0].y, a[NV - 1].y)),
-                                                     pack_bf16(swiglu(a[0].z, a[NV - 1].z), swiglu(a[0].w, a[NV - 1].w)));
-    else
-        *reinterpret_cast<uint2*>(orow) = make_uint2(pack_f16(a[0].x, a[0].y), pack_f16(a[0].z, a[0].w));
 }
 
 template <bool SWIGLU, bool TAIL>
@@ -1241,7 +1240,7 @@ static hipError_t launch_w4(const GemmArgs& a, int max_mtiles, hipStream_t s)
         const int max_tail = (int)std::min<long>(total, grid - 1);
         if (max_tail > 0) {
             kern_tail<<<grid, 256, LDS, s>>>(g);
-            gemm_tail_sum_kernel<SWIGLU><<<max_tail * 64, 256, 0, s>>>(g, grid);
+            gemm_tail_sum_kernel<SWIGLU><<<std::min(max_tail * 64, 2048), 256, 0, s>>>(g, grid);
         }
     }
     return hipGetLastError();
