@@ -142,6 +142,7 @@ struct Tile {
     int unit, row0, nrows, nt, n0;
     int kslice, ks;                             // this block multiplies slice kslice of ks slices of K
     int part;                                   // slot in GemmArgs::partial the result goes to, or -1: to the output
+    int half;                                   // column-half tail of the four-wave kernel: which half of the tile
     const bf16_t *Wa, *Wb;
 };
 
@@ -159,6 +160,7 @@ __device__ __forceinline__ bool decode_tile(const GemmArgs& p, Tile& t)
     t.kslice = Lfull / tiles;
     t.ks = p.ksplit;
     t.part = -1;
+    t.half = 0;
     const int L = Lfull - t.kslice * tiles;
     // Super-tiles of group_m M tiles x all N tiles, M fastest: the ~32 blocks an XCD runs at a time
     // cover group_m x (32/group_m) tiles and share their A and B panels in that XCD's L2.
@@ -742,7 +744,15 @@ __device__ __forceinline__ void tile_coords(const GemmArgs& p, int n_mt, int L, 
     mt = mt_first + (rem - nt * gsz);
 }
 
-template <int BNC, bool TAIL>
+// Left-over tiles that are not cut along K: when there are at most G/2 of them, each is cut in two along N
+// instead (two blocks, 256 rows x half the columns each: no partial sums, half a tile time).
+__host__ __device__ inline bool tail_halves(int G, int rem, int nk_all)
+{
+    return rem > 0 && 2 * rem <= G && nk_all >= 8 && tail_split(G, rem, nk_all) == 1;
+}
+
+// MODE 0: whole tiles (the main launch); 1: K slices of the left-over tiles; 2: column halves of them.
+template <int BNC, int MODE>
 __device__ __forceinline__ bool decode_tile_at(const GemmArgs& p, int xcd, int bi, int slots, Tile& t)
 {
     const int n_mt = p.table[0];
@@ -751,7 +761,8 @@ __device__ __forceinline__ bool decode_tile_at(const GemmArgs& p, int xcd, int b
     t.ks = p.ksplit;
     t.part = -1;
     t.kslice = 0;
-    if (!TAIL && p.partial == nullptr) {
+    t.half = 0;
+    if (MODE == 0 && p.partial == nullptr) {
         const int total = tiles * p.ksplit;
         const int chunk = (total + 7) >> 3;
         if (bi >= chunk) return false;
@@ -761,23 +772,33 @@ __device__ __forceinline__ bool decode_tile_at(const GemmArgs& p, int xcd, int b
         L = Lfull - t.kslice * tiles;
     } else {
         // Whole tiles: every XCD sweeps its contiguous chunk (a multiple of its `slots` blocks), then one more
-        // round for the tiles left over if they are not split.  A split tail is the work of the TAIL
-        // instantiation, launched next: one slice per block, slice-major, so that the blocks of an XCD work
-        // on the same slices of K.
+        // round for the tiles left over if they are not cut.  Cut tiles are the work of the other two
+        // instantiations, launched next, one piece per block: K slices slice-major, so that the blocks of an
+        // XCD work on the same slices of K; column halves side by side, so that they share the A rows in L2.
         const int G = slots * 8;
         const int t_full = tiles / G * G, chunk = t_full >> 3;
         const int rem = tiles - t_full;
         const int sl = tail_split(G, rem, p.K / 64);
-        if (!TAIL && bi < chunk) {
+        const bool halves = tail_halves(G, rem, p.K / 64);
+        if (MODE == 0 && bi < chunk) {
             L = xcd * chunk + bi;
         } else {
-            const int round = TAIL ? bi : bi - chunk;
-            if (round >= slots || (sl > 1) != TAIL) return false;
+            const int round = MODE == 0 ? bi - chunk : bi;
+            if (round >= slots) return false;
             const int c = xcd * slots + round;
-            if (c >= rem * sl) return false;
-            const int pz = c / rem, j = c - pz * rem;
-            L = t_full + j;
-            if (TAIL) { t.kslice = pz; t.ks = sl; t.part = j * sl + pz; }
+            if (MODE == 0) {
+                if (sl > 1 || halves || c >= rem) return false;
+                L = t_full + c;
+            } else if (MODE == 1) {
+                if (sl <= 1 || c >= rem * sl) return false;
+                const int pz = c / rem, j = c - pz * rem;
+                L = t_full + j;
+                t.kslice = pz; t.ks = sl; t.part = j * sl + pz;
+            } else {
+                if (!halves || c >= 2 * rem) return false;
+                L = t_full + (c >> 1);
+                t.half = c & 1;
+            }
         }
     }
     int mt;
@@ -859,16 +880,24 @@ __global__ void __launch_bounds__(256) gemm_tail_sum_kernel(GemmArgs p, int G)
     }
 }
 
-template <bool SWIGLU, bool TAIL>
+template <bool SWIGLU, int MODE>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) ffn_gemm_w4_kernel(GemmArgs p)
 {
     constexpr int BM = 256, BN = 256, BK = 64, NW = 4;
     using L = Lds<BK>;
-    constexpr int TM = 128, TN = 128, FM = TM / 16, FN = TN / 16;
+    // MODE 2 (column half of a tile): the wave tile is 128 x 64, half the MFMAs and half the B rows per k tile;
+    // loads, buffers, barrier and the order of the load slots are those of the full tile at half the spacing
+    constexpr int TM = 128, TN = MODE == 2 ? 64 : 128, FM = TM / 16, FN = TN / 16;
     constexpr int RB = L::RB, RPG = L::RPG;
     constexpr int ABUF = BM * RB, BBUF = BN * RB;        // 32 KiB each
     constexpr int B_BASE = 2 * ABUF;
-    constexpr int HL = BM / RPG / NW;                    // 8 loads of A rows and 8 of B rows per wave and tile
+    constexpr int HL = BM / RPG / NW;                    // 8 loads of A rows per wave and k tile
+    constexpr int HLB = MODE == 2 ? HL / 2 : HL;         // and 8 (column half: 4) of B rows
+    constexpr int NM = FM * FN;                          // MFMAs of one step (64; column half: 32)
+    constexpr int EV = NM / 8;                           // MFMAs per load slot
+    constexpr int BAR = 6 * EV;                          // the barrier: three quarters into step 0
+    constexpr int NRD = 2 * (FM + FN);                   // fragment reads of a step, one per two MFMAs
+    static_assert(NRD <= BAR, "the fragment reads of a step end before its barrier");
     constexpr int BNC = SWIGLU ? BN / 2 : BN;
     // GEMM1 gathers its A rows (tokens of the unit); GEMM2 reads consecutive rows of H, which is padded by
     // one tile of rows so that the rows of a ragged tile need no clamping.
@@ -880,10 +909,12 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
     const int xcd = blockIdx.x & 7, slots = gridDim.x >> 3;
     int bi = blockIdx.x >> 3;
     Tile t;
-    if (!decode_tile_at<BNC, TAIL>(p, xcd, bi, slots, t)) return;
+    if (!decode_tile_at<BNC, MODE>(p, xcd, bi, slots, t)) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);
-    const int wm = wave >> 1, wn = wave & 1;
+    // wave tile: rows wm * 128 .., B-tile rows wn * TN ..  (column half h of a tile: the 64-row quarters 2h, 2h+1)
+    const int wm = wave >> 1, wn = MODE == 2 ? 2 * t.half + (wave & 1) : (wave & 1);
+    const int q0 = MODE == 2 ? (HL / 2) * __builtin_amdgcn_readfirstlane(t.half) : 0;   // first B load of the half
 
     // Load i of a wave covers rows (wave + 4 i) * 8 .. + 8 of the A (or B) tile.  An address is a
     // wave-uniform base (scalar registers) plus a 32-bit lane offset: gathered A rows have one lane offset
@@ -895,7 +926,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
     const unsigned offB = (unsigned)((long)r8 * p.K * 2 + csw * 16);
     unsigned offA[NOA];
     const bf16_t* baseA[NBA];
-    const bf16_t* baseB[HL];
+    const bf16_t* baseB[HLB];
     int nk = 0, last = 0;
 
     // Source rows of the 64 A rows this wave loads per k tile (gathered A only), one per lane: lane k holds
@@ -922,8 +953,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
                     uniform_ptr(p.A + (size_t)(tt.row0 + (wave_s + i * NW) * RPG) * p.lda + (size_t)k_first * BK);
         }
 #pragma unroll
-        for (int q = 0; q < HL; ++q) {
-            const int g = wave_s + NW * q;                // 8-row group inside the B tile, 0..31
+        for (int q = 0; q < HLB; ++q) {
+            const int g = wave_s + NW * (q + q0);         // 8-row group inside the B tile, 0..31
             const bf16_t* W = tt.Wa;
             int col0;
             if (SWIGLU) {
@@ -946,20 +977,20 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
     };
     auto load_b = [&](int q, int tile, int bbuf) {
         const char* src = reinterpret_cast<const char*>(baseB[q] + (long)tile * BK) + offB;
-        char* dst = smem + B_BASE + bbuf * BBUF + (wave_s + q * NW) * 1024;
+        char* dst = smem + B_BASE + bbuf * BBUF + (wave_s + (q + q0) * NW) * 1024;
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                          (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
     };
-    // first k tiles of an output tile: tiles 0 and 1, and the first two B loads of tile 2 (4 * HL + 2 loads)
+    // first k tiles of an output tile: tiles 0 and 1, and the first two B loads of tile 2
     auto issue_prologue = [&]() {
 #pragma unroll
         for (int i = 0; i < HL; ++i) load_a(i, 0, 0);
 #pragma unroll
-        for (int q = 0; q < HL; ++q) load_b(q, 0, 0);
+        for (int q = 0; q < HLB; ++q) load_b(q, 0, 0);
 #pragma unroll
         for (int i = 0; i < HL; ++i) load_a(i, min(1, last), 1);
 #pragma unroll
-        for (int q = 0; q < HL; ++q) load_b(q, min(1, last), 1);
+        for (int q = 0; q < HLB; ++q) load_b(q, min(1, last), 1);
 #pragma unroll
         for (int q = 0; q < 2; ++q) load_b(q, min(2, last), 2);
     };
@@ -984,7 +1015,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
         // the next output tile of this block, or this one again when there is none (its index load is
         // issued either way, so the number of loads in flight does not depend on it)
         Tile tn;
-        const bool has_next = decode_tile_at<BNC, TAIL>(p, xcd, bi + slots, slots, tn);
+        const bool has_next = decode_tile_at<BNC, MODE>(p, xcd, bi + slots, slots, tn);
         if (!has_next) tn = t;
         const int gnext = GATHER ? gather_rows(tn) : 0;
 
@@ -1003,9 +1034,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
             for (int j = 0; j < FN; ++j) asm volatile("" : "+a"(acc[i][j]));
 
         if (nk > 0) {
-            // k tile 0 has landed once at most the 2 * HL + 2 younger loads of the first batch, and the index
+            // k tile 0 has landed once at most the HL + HLB + 2 younger loads of the first batch, and the index
             // load after them, are in flight (stores of the previous epilogue only make this wait longer)
-            __builtin_amdgcn_s_waitcnt(vmcnt_imm(2 * HL + 2 + (GATHER ? 1 : 0)));
+            __builtin_amdgcn_s_waitcnt(vmcnt_imm(HL + HLB + 2 + (GATHER ? 1 : 0)));
             lds_barrier();
 #pragma unroll
             for (int i = 0; i < FM; ++i) read_frag_a(0, 0, i, 0);
@@ -1029,31 +1060,32 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
 #pragma unroll
                         for (int j = 0; j < FN; ++j) {
                             const int mi = i * FN + j;
-                            if (st == 0 && mi == 48) {
+                            if (st == 0 && mi == BAR) {
                                 // my reads of tile kt are done (both its buffers may be refilled) and my loads
-                                // of tile kt+1 have landed: everything but the HL youngest requests
+                                // of tile kt+1 have landed: everything but the HLB youngest requests
                                 __builtin_amdgcn_sched_barrier(0);
-                                __builtin_amdgcn_s_waitcnt(vmcnt_lgkm0_imm(HL));
+                                __builtin_amdgcn_s_waitcnt(vmcnt_lgkm0_imm(HLB));
                                 lds_barrier();
                                 __builtin_amdgcn_sched_barrier(0);
                             }
                             acc[i][j] =
                                 __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[st][j], fa[st][i], acc[i][j], 0, 0, 0);
-                            if (mi < 32 && (mi & 1) == 0) {       // 16 fragment reads, one per two MFMAs
+                            if (mi < NRD && (mi & 1) == 0) {      // fragment reads, one per two MFMAs
                                 const int r = mi >> 1;
                                 __builtin_amdgcn_sched_barrier(0);
                                 if (r < FN) read_frag_b(b_rd, st ^ 1, r, st ^ 1);
                                 else read_frag_a(a_rd, st ^ 1, r - FN, st ^ 1);
                                 __builtin_amdgcn_sched_barrier(0);
                             }
-                            // One direct load every eight MFMAs (closer together they queue up in the texture
-                            // path and hold the wave).  After the barrier: the A rows of tile kt+2 into the A
-                            // buffer just left, then the B rows of tile kt+3 into tile kt's B buffer, the last six
-                            // of them during the first three quarters of the next tile's first step.
-                            if ((mi & 7) == 0) {
-                                const int slot = mi >> 3;
+                            // One direct load per slot of EV MFMAs (eight for the full tile: closer together they
+                            // queue up in the texture path and hold the wave).  After the barrier: the A rows of
+                            // tile kt+2 into the A buffer just left, then the B rows of tile kt+3 into tile kt's
+                            // B buffer, all but the first two of them during the first three quarters of the
+                            // next tile's first step.
+                            if (mi % EV == 0) {
+                                const int slot = mi / EV;
                                 __builtin_amdgcn_sched_barrier(0);
-                                if (st == 0 && slot < 6) load_b(slot + 2, t2, b_nn);
+                                if (st == 0 && slot < HLB - 2) load_b(slot + 2, t2, b_nn);
                                 if (st == 0 && slot >= 6) load_a(slot - 6, t2, a_cur);
                                 if (st == 1 && slot < 6) load_a(slot + 2, t2, a_cur);
                                 if (st == 1 && slot >= 6) load_b(slot - 6, t3, b_cur);
@@ -1089,10 +1121,11 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
             // lane-derived epilogue values are recomputed per tile instead of living through the main loop
             int lane_e;
             asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(lane_e));
-            if (TAIL)
-                store_partial16<FM, FN, TM, TN>(p.partial + (size_t)tcur.part * 65536, acc, wave_s >> 1, wave_s & 1, lane_e);
+            const int wn_e = MODE == 2 ? q0 / 2 + (wave_s & 1) : (wave_s & 1);
+            if (MODE == 1)
+                store_partial16<FM, FN, TM, TN>(p.partial + (size_t)tcur.part * 65536, acc, wave_s >> 1, wn_e, lane_e);
             else
-                store_tile16<FM, FN, TM, TN, SWIGLU>(p, tcur, acc, wave_s >> 1, wave_s & 1, lane_e);
+                store_tile16<FM, FN, TM, TN, SWIGLU>(p, tcur, acc, wave_s >> 1, wn_e, lane_e);
         }
         if (!has_next) break;
     }
@@ -1211,13 +1244,16 @@ static hipError_t launch_w4(const GemmArgs& a, int max_mtiles, hipStream_t s)
     constexpr int LDS = 160 * 1024;
     static bool attr_set = false;
     static int n_cu = 0;
-    auto kern = ffn_gemm_w4_kernel<SWIGLU, false>;
-    auto kern_tail = ffn_gemm_w4_kernel<SWIGLU, true>;
+    auto kern = ffn_gemm_w4_kernel<SWIGLU, 0>;
+    auto kern_tail = ffn_gemm_w4_kernel<SWIGLU, 1>;
+    auto kern_half = ffn_gemm_w4_kernel<SWIGLU, 2>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
         if (e != hipSuccess) return e;
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern_tail), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        if (e != hipSuccess) return e;
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern_half), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
         if (e != hipSuccess) return e;
         int dev = 0;
         e = hipGetDevice(&dev);
@@ -1235,10 +1271,11 @@ static hipError_t launch_w4(const GemmArgs& a, int max_mtiles, hipStream_t s)
     if (g.ksplit != 1 || grid > g.partial_cap) g.partial = nullptr;
     kern<<<grid, 256, LDS, s>>>(g);
     if (g.partial) {
-        // the tiles left over after the last full round of `grid` tiles, cut along K (one slice per block),
-        // then summed; which of the two it is, if any, only the tile table on the device knows
+        // the tiles left over after the last full round of `grid` tiles: cut along K (one slice per block,
+        // then summed) or in two along N; which it is, if any, only the tile table on the device knows
         const int max_tail = (int)std::min<long>(total, grid - 1);
         if (max_tail > 0) {
+            kern_half<<<grid, 256, LDS, s>>>(g);
             kern_tail<<<grid, 256, LDS, s>>>(g);
             gemm_tail_sum_kernel<SWIGLU><<<std::min(max_tail * 64, 2048), 256, 0, s>>>(g, grid);
         }
