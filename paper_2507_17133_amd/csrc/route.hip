@@ -289,10 +289,13 @@ __device__ __forceinline__ void wait_vmcnt_at_most(int n)
     else __builtin_amdgcn_s_waitcnt(0x0F70);
 }
 
-template <int TG, int NTH>
+template <int TG, int NTH, int KB>
 __global__ void __launch_bounds__(TG * 128) gate_tiled_kernel(GateArgs p)
 {
+    // KB = k elements per stage: 64 (rows of 128 bytes, whole cache lines: what bounds this kernel is the number
+    // of line requests a CU keeps in flight, not bytes) where three such stages fit the LDS, else 32
     constexpr int NWV = 2 * TG;
+    constexpr int RB = KB * 2, CPR = RB / 16, WR = 256 / RB, RPL = 1024 / RB, NSL = KB / 32;
     const int NST = p.n_stage;                          // LDS stages: as many as fit, at most 8
     extern __shared__ __attribute__((aligned(16))) char gsm[];
     __shared__ int hist[kMaxExperts];
@@ -302,21 +305,22 @@ __global__ void __launch_bounds__(TG * 128) gate_tiled_kernel(GateArgs p)
     const int n_tiles = p.m_pad >> 4;
     const int w_rows = 3 * p.m_pad;                     // LDS rows of one stage: [piece][expert], then the x rows
     const int rows = w_rows + 16 * TG;
-    const int groups = rows >> 4;                       // 16 rows (1 KiB) per wave-wide load
-    const int stage_bytes = rows * 64;
+    const int groups = rows / RPL;                      // RPL rows (1 KiB) per wave-wide load
+    const int stage_bytes = rows * RB;
     for (int i = tid; i < p.m_pad; i += TG * 128) hist[i] = 0;
 
-    // loader: wave w moves row groups w, w+NWV, ...; lane -> row lane/4, 16-byte slot lane%4 holding
-    // chunk (lane%4) ^ ((row/4)&3)  (conflict-free ds_read_b128 on the 64-bank LDS)
-    const int ksteps = p.d >> 5;
+    // loader: wave w moves row groups w, w+NWV, ...; lane -> row lane/CPR, 16-byte slot lane%CPR holding
+    // chunk (lane%CPR) ^ ((row/WR)&(CPR-1))  (conflict-free ds_read_b128 on the 64-bank LDS)
+    const int ksteps = p.d / KB;
     // the source address of every load of a stage is fixed up to the k offset: computed once, not per step
-    constexpr int MAXS = (3 * kMaxExperts + 16 * TG + 16 * NWV - 1) / (16 * NWV);
+    constexpr int MAXM = KB == 64 ? 128 : kMaxExperts;  // the launcher takes KB = 64 for at most 128 experts
+    constexpr int MAXS = (3 * MAXM + 16 * TG + RPL * NWV - 1) / (RPL * NWV);
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);
     const unsigned short* srcp[MAXS];
 #pragma unroll
     for (int i = 0; i < MAXS; ++i) {
-        const int row = min((wave + i * NWV) * 16 + (lane >> 2), rows - 1);
-        const int chunk = (lane & 3) ^ ((row >> 2) & 3);
+        const int row = min((wave + i * NWV) * RPL + lane / CPR, rows - 1);
+        const int chunk = (lane % CPR) ^ ((row / WR) & (CPR - 1));
         const unsigned short* src;
         if (row < w_rows) src = p.split + (size_t)row * p.d;
         else src = reinterpret_cast<const unsigned short*>(p.x) + (size_t)min(t0 + row - w_rows, p.T - 1) * p.d;
@@ -327,7 +331,7 @@ __global__ void __launch_bounds__(TG * 128) gate_tiled_kernel(GateArgs p)
 #pragma unroll
         for (int i = 0; i < MAXS; ++i)
             if (wave_s + i * NWV < groups)
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(srcp[i] + (ks << 5)),
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(srcp[i] + ks * KB),
                                                  (__attribute__((address_space(3))) void*)(dst + i * NWV * 1024), 16, 0, 0);
     };
 
@@ -335,21 +339,21 @@ __global__ void __launch_bounds__(TG * 128) gate_tiled_kernel(GateArgs p)
     f32x4 acc[NTH];
     bool tile_ok[NTH];
     int boff[NTH];
+    // the swizzle term of a row depends on the lane only: expert tiles start at multiples of 16 rows, the x
+    // rows at 3 * m_pad + 16 * tg, and 16 / WR is a multiple of CPR
+    const int swz = ((lane & 15) / WR) & (CPR - 1);
 #pragma unroll
     for (int nt = 0; nt < NTH; ++nt) {
         const int tile = eh * NTH + nt;
         tile_ok[nt] = tile < n_tiles;
-        const int erow = (tile_ok[nt] ? tile : 0) * 16 + (lane & 15);
-        boff[nt] = erow * 64 + (((lane >> 4) ^ ((erow >> 2) & 3)) << 4);
+        boff[nt] = ((tile_ok[nt] ? tile : 0) * 16 + (lane & 15)) * RB;
         acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int v = 0; v < 4; ++v) sum[nt][v] = 0.0;
     }
-    const int arow = w_rows + tg * 16 + (lane & 15);
-    const int aoff = arow * 64 + (((lane >> 4) ^ ((arow >> 2) & 3)) << 4);
+    const int aoff = (w_rows + tg * 16 + (lane & 15)) * RB;
     // All loads of the loop go to LDS and complete in order per wave: at the top of step ks the loads of
-    // stage ks are older than those of the later stages, which may stay in flight.  A step is little work
-    // (a dozen MFMAs per wave), so the depth of this queue, not the arithmetic, sets the pace.
+    // stage ks are older than those of the later stages, which may stay in flight.
     const int young = groups / NWV;                     // loads of one stage every wave issues at least
     for (int q = 0; q < NST - 1; ++q)
         if (q < ksteps) issue(q, q);
@@ -364,20 +368,26 @@ __global__ void __launch_bounds__(TG * 128) gate_tiled_kernel(GateArgs p)
         const char* St = gsm + buf * stage_bytes;
         buf_ld = buf;
         buf = buf + 1 == NST ? 0 : buf + 1;
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(St + aoff);
-        // low piece first in every expert tile (the sum of a tile is taken in that order); piece by piece
-        // across the tiles, so that consecutive MFMAs do not wait for each other's result
-        bf16x8 b[3][NTH];
 #pragma unroll
-        for (int pz = 0; pz < 3; ++pz)
+        for (int sl = 0; sl < NSL; ++sl) {              // 32-wide k slices of the stage
+            const int coff = ((sl * 4 + (lane >> 4)) ^ swz) << 4;
+            const bf16x8 a = *reinterpret_cast<const bf16x8*>(St + aoff + coff);
+            // low piece first in every expert tile (the sum of a tile is taken in that order); piece by piece
+            // across the tiles, so that consecutive MFMAs do not wait for each other's result
+            bf16x8 b[3][NTH];
 #pragma unroll
-            for (int nt = 0; nt < NTH; ++nt)
-                b[pz][nt] = *reinterpret_cast<const bf16x8*>(St + pz * p.m_pad * 64 + boff[nt]);
+            for (int pz = 0; pz < 3; ++pz)
 #pragma unroll
-        for (int pz = 2; pz >= 0; --pz)
+                for (int nt = 0; nt < NTH; ++nt)
+                    b[pz][nt] = *reinterpret_cast<const bf16x8*>(St + pz * p.m_pad * RB + boff[nt] + coff);
 #pragma unroll
-            for (int nt = 0; nt < NTH; ++nt) acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b[pz][nt], acc[nt], 0, 0, 0);
-        if ((ks & 1) == 1 || ks + 1 == ksteps) {
+            for (int pz = 2; pz >= 0; --pz)
+#pragma unroll
+                for (int nt = 0; nt < NTH; ++nt)
+                    acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b[pz][nt], acc[nt], 0, 0, 0);
+        }
+        // into the fp64 sums after every 64 k (d is a multiple of 64)
+        if (KB == 64 || (ks & 1) == 1 || ks + 1 == ksteps) {
 #pragma unroll
             for (int nt = 0; nt < NTH; ++nt) {
 #pragma unroll
@@ -694,30 +704,32 @@ hipError_t launch_route(const Dims& D, const bf16_t* x, const float* gate_w, con
         const int half_tiles = ceil_div(n_tiles, 2);
         const int tgw = D.T >= 64 * 192 ? 4 : (D.T >= 32 * 192 ? 2 : 0);
         if (n_tiles >= 4 && tgw != 0) {
-            const int stage = (3 * D.m_pad + 16 * tgw) * 64;
+            const int rows = 3 * D.m_pad + 16 * tgw;
+            const bool wide = D.m_pad <= 128 && 3 * rows * 128 <= kGateLds - 1024;    // 64-wide k stages fit
+            const int stage = rows * (wide ? 128 : 64);
             g.n_stage = std::max(3, std::min(8, (kGateLds - 1024) / stage));
             const int lds = std::max(g.n_stage * stage, 16 * tgw * D.m_pad * 4);
             const int blocks = ceil_div(D.T, 16 * tgw);
             hipError_t e = hipSuccess;
-#define BMOE_GATE_TILED(TG_, NTH_)                                                                               \
+#define BMOE_GATE_TILED(TG_, NTH_, KB_)                                                                          \
             do {                                                                                                   \
                 static bool attr_set = false;                                                                      \
                 if (!attr_set) {                                                                                   \
-                    e = hipFuncSetAttribute(reinterpret_cast<const void*>(gate_tiled_kernel<TG_, NTH_>),           \
+                    e = hipFuncSetAttribute(reinterpret_cast<const void*>(gate_tiled_kernel<TG_, NTH_, KB_>),      \
                                             hipFuncAttributeMaxDynamicSharedMemorySize,                            \
                                             kGateLds - 1024);                                                      \
                     attr_set = e == hipSuccess;                                                                    \
                 }                                                                                                  \
-                if (e == hipSuccess) gate_tiled_kernel<TG_, NTH_><<<blocks, TG_ * 128, lds, s>>>(g);               \
+                if (e == hipSuccess) gate_tiled_kernel<TG_, NTH_, KB_><<<blocks, TG_ * 128, lds, s>>>(g);          \
             } while (0)
             if (tgw == 4) {
-                if (half_tiles <= 2) BMOE_GATE_TILED(4, 2);
-                else if (half_tiles <= 4) BMOE_GATE_TILED(4, 4);
-                else BMOE_GATE_TILED(4, 8);
+                if (half_tiles <= 2) { if (wide) BMOE_GATE_TILED(4, 2, 64); else BMOE_GATE_TILED(4, 2, 32); }
+                else if (half_tiles <= 4) { if (wide) BMOE_GATE_TILED(4, 4, 64); else BMOE_GATE_TILED(4, 4, 32); }
+                else BMOE_GATE_TILED(4, 8, 32);
             } else {
-                if (half_tiles <= 2) BMOE_GATE_TILED(2, 2);
-                else if (half_tiles <= 4) BMOE_GATE_TILED(2, 4);
-                else BMOE_GATE_TILED(2, 8);
+                if (half_tiles <= 2) { if (wide) BMOE_GATE_TILED(2, 2, 64); else BMOE_GATE_TILED(2, 2, 32); }
+                else if (half_tiles <= 4) { if (wide) BMOE_GATE_TILED(2, 4, 64); else BMOE_GATE_TILED(2, 4, 32); }
+                else BMOE_GATE_TILED(2, 8, 32);
             }
 #undef BMOE_GATE_TILED
             if (e != hipSuccess) return e;
