@@ -15,7 +15,9 @@
 // of tiles, ordered so that the blocks it runs at a time share A and B panels in its own L2.
 //
 // Kernels, by tile height (chosen on the host from the expected rows per unit):
-//   256 rows  ffn_gemm_w4_kernel   four waves, one per SIMD, 128x128 wave tiles, 16x16x32 MFMA, persistent
+//   256 rows  ffn_gemm_w4_kernel   four waves, one per SIMD, 128x128 wave tiles, 16x16x32 MFMA, persistent;
+//                                  two more instantiations for the tiles left over after the last full round:
+//                                  cut along K (fp32 partial tiles, gemm_tail_sum_kernel) or in two along N
 //             ffn_gemm_rs_kernel   eight waves, register-staged; stand-in when A offsets exceed 32 bits
 //   128 rows  ffn_gemm_pp_kernel   eight waves in two groups that alternate memory and MFMA phases
 //   64, 32    ffn_gemm_kernel      four waves, plain multi-stage ring (decode: weight streaming bound)
@@ -23,7 +25,6 @@
 
 #include <algorithm>
 #include <cstdlib>
-#include <type_traits>
 
 namespace bmoe {
 
@@ -32,13 +33,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ unsigned short f2bf(float f)
-{
-    unsigned int u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (unsigned short)(u >> 16);
-}
-__device__ __forceinline__ float bf2f(unsigned short b) { return __uint_as_float(((unsigned int)b) << 16); }
 // two floats -> two bf16 (round to nearest even) in one 32-bit word, first value in the low half
 __device__ __forceinline__ unsigned pack_bf16(float lo, float hi)
 {
@@ -573,12 +567,6 @@ __device__ __forceinline__ const bf16_t* uniform_ptr(const bf16_t* ptr)
     const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
     const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
     return reinterpret_cast<const bf16_t*>(((unsigned long long)hi << 32) | lo);
-}
-
-// Same with a wave-uniform base address in scalar registers and a 32-bit byte offset per lane.
-__device__ __forceinline__ void load_stage_s(u32x4& dst, const bf16_t* base, unsigned off)
-{
-    asm volatile("global_load_dwordx4 %0, %1, %2" : "=v"(dst) : "v"(off), "s"(base));
 }
 
 template <int BM, bool SWIGLU>

@@ -141,6 +141,61 @@ __device__ __forceinline__ void topk_token(const GateArgs& p, const float* logit
     if (lane == 0 && p.near_tie != nullptr) p.near_tie[t] = any_close != 0ull ? 1 : 0;
 }
 
+// The same for four tokens at a time: token `row` = lane >> 4 of the four is handled by the 16 lanes of its
+// row, lane r of the row holding experts r, r+16, ...; every reduction stays inside the row (rotations), so
+// the four selections run side by side.  Needs K + 1 <= 16 (lane j of the row keeps the j-th winner).
+// tl: this row's token inside the block's logit array, t: its global index, valid: whether it exists.
+__device__ __forceinline__ void topk_rows(const GateArgs& p, const float* logit, int tl, int t, bool valid, int lane, int* hist)
+{
+    const int K = p.K, r = lane & 15;
+    const int n_pick = K < p.m ? K + 1 : K;
+    const float* logit_row = logit + tl * p.m_pad;
+    float v[16];
+    unsigned taken = 0;
+#pragma unroll
+    for (int c = 0; c < 16; ++c) {
+        const int e = r + 16 * c;
+        v[c] = e < p.m ? logit_row[e] : 0.0f;
+        if (e >= p.m) taken |= 1u << c;
+    }
+    float my_v = 0.0f;
+    int my_i = 0;
+    for (int j = 0; j < n_pick; ++j) {
+        float bv = 0.0f;
+        int bi = 0x7fffffff;
+#pragma unroll
+        for (int c = 0; c < 16; ++c) {
+            if (taken & (1u << c)) continue;
+            if (bi == 0x7fffffff || v[c] > bv) { bv = v[c]; bi = r + 16 * c; }
+        }
+        better(bv, bi, dpp_f<0x121>(bv), dpp_i<0x121>(bi));
+        better(bv, bi, dpp_f<0x122>(bv), dpp_i<0x122>(bi));
+        better(bv, bi, dpp_f<0x124>(bv), dpp_i<0x124>(bi));
+        better(bv, bi, dpp_f<0x128>(bv), dpp_i<0x128>(bi));
+        if ((bi & 15) == r) taken |= 1u << (bi >> 4);
+        if (r == j) { my_v = bv; my_i = bi; }
+    }
+    const float top = __shfl(my_v, lane & ~15);
+    float num = 0.0f;
+    if (r < K) num = p.score_fn == 0 ? expf(my_v - top) : 1.0f / (1.0f + expf(-my_v));
+    float den = num;
+    den += dpp_f<0x121>(den);
+    den += dpp_f<0x122>(den);
+    den += dpp_f<0x124>(den);
+    den += dpp_f<0x128>(den);
+    const float nxt = __shfl(my_v, (lane & ~15) | ((r + 1) & 15));
+    const bool close = r + 1 < n_pick && (my_v - nxt) < 1e-6f;
+    const unsigned long long any_close = __ballot(close);
+    if (valid) {
+        if (r < K) {
+            p.topk_idx[(size_t)t * K + r] = my_i;
+            p.topk_w[(size_t)t * K + r] = num / den;
+            atomicAdd(&hist[my_i], 1);
+        }
+        if (r == 0 && p.near_tie != nullptr) p.near_tie[t] = ((any_close >> (lane & 48)) & 0xFFFFull) != 0ull ? 1 : 0;
+    }
+}
+
 template <int NTW>
 __global__ void __launch_bounds__(1024) gate_topk_kernel(GateArgs p)
 {
@@ -411,9 +466,18 @@ __global__ void __launch_bounds__(TG * 128) gate_tiled_kernel(GateArgs p)
         }
     }
     __syncthreads();
-    for (int tok = wave; tok < 16 * TG; tok += NWV) {
-        if (t0 + tok >= p.T) break;
-        topk_token(p, logit + tok * p.m_pad, t0 + tok, lane, hist);
+    if (p.K + 1 <= 16) {
+        // four tokens per wavefront at a time
+        for (int tok = wave * 4; tok < 16 * TG; tok += NWV * 4) {
+            const int tl = tok + (lane >> 4);
+            const bool valid = t0 + tl < p.T;
+            topk_rows(p, logit, valid ? tl : tok, t0 + tl, valid && t0 + tok < p.T, lane, hist);
+        }
+    } else {
+        for (int tok = wave; tok < 16 * TG; tok += NWV) {
+            if (t0 + tok >= p.T) break;
+            topk_token(p, logit + tok * p.m_pad, t0 + tok, lane, hist);
+        }
     }
     __syncthreads();
     for (int i = tid; i < p.m; i += TG * 128)
