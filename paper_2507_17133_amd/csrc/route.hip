@@ -344,9 +344,12 @@ __device__ __forceinline__ void wait_vmcnt_at_most(int n)
     else __builtin_amdgcn_s_waitcnt(0x0F70);
 }
 
-template <int TG, int NTH, int KB>
+template <int TG, int NTH, int KB, int MT>
 __global__ void __launch_bounds__(TG * 128) gate_tiled_kernel(GateArgs p)
 {
+    // A wave multiplies MT token tiles (16 tokens each) by NTH expert tiles: its 2 TG / (TG / MT) = 2 MT
+    // expert groups partition the experts.  MT = 2 halves the B fragments read from LDS per MFMA.
+    static_assert(TG % MT == 0, "token tiles per wave");
     // KB = k elements per stage: 64 (rows of 128 bytes, whole cache lines: what bounds this kernel is the number
     // of line requests a CU keeps in flight, not bytes) where three such stages fit the LDS, else 32
     constexpr int NWV = 2 * TG;
@@ -355,7 +358,7 @@ __global__ void __launch_bounds__(TG * 128) gate_tiled_kernel(GateArgs p)
     extern __shared__ __attribute__((aligned(16))) char gsm[];
     __shared__ int hist[kMaxExperts];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int tg = wave % TG, eh = wave / TG;
+    const int tg = (wave % (TG / MT)) * MT, eh = wave / (TG / MT);   // first token tile, expert group
     const int t0 = blockIdx.x * (16 * TG);
     const int n_tiles = p.m_pad >> 4;
     const int w_rows = 3 * p.m_pad;                     // LDS rows of one stage: [piece][expert], then the x rows
@@ -390,8 +393,8 @@ __global__ void __launch_bounds__(TG * 128) gate_tiled_kernel(GateArgs p)
                                                  (__attribute__((address_space(3))) void*)(dst + i * NWV * 1024), 16, 0, 0);
     };
 
-    double sum[NTH][4];
-    f32x4 acc[NTH];
+    double sum[MT][NTH][4];
+    f32x4 acc[MT][NTH];
     bool tile_ok[NTH];
     int boff[NTH];
     // the swizzle term of a row depends on the lane only: expert tiles start at multiples of 16 rows, the x
@@ -402,9 +405,12 @@ __global__ void __launch_bounds__(TG * 128) gate_tiled_kernel(GateArgs p)
         const int tile = eh * NTH + nt;
         tile_ok[nt] = tile < n_tiles;
         boff[nt] = ((tile_ok[nt] ? tile : 0) * 16 + (lane & 15)) * RB;
-        acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int v = 0; v < 4; ++v) sum[nt][v] = 0.0;
+        for (int mt = 0; mt < MT; ++mt) {
+            acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int v = 0; v < 4; ++v) sum[mt][nt][v] = 0.0;
+        }
     }
     const int aoff = (w_rows + tg * 16 + (lane & 15)) * RB;
     // All loads of the loop go to LDS and complete in order per wave: at the top of step ks the loads of
@@ -426,7 +432,9 @@ __global__ void __launch_bounds__(TG * 128) gate_tiled_kernel(GateArgs p)
 #pragma unroll
         for (int sl = 0; sl < NSL; ++sl) {              // 32-wide k slices of the stage
             const int coff = ((sl * 4 + (lane >> 4)) ^ swz) << 4;
-            const bf16x8 a = *reinterpret_cast<const bf16x8*>(St + aoff + coff);
+            bf16x8 a[MT];
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) a[mt] = *reinterpret_cast<const bf16x8*>(St + aoff + mt * 16 * RB + coff);
             // low piece first in every expert tile (the sum of a tile is taken in that order); piece by piece
             // across the tiles, so that consecutive MFMAs do not wait for each other's result
             bf16x8 b[3][NTH];
@@ -438,17 +446,21 @@ __global__ void __launch_bounds__(TG * 128) gate_tiled_kernel(GateArgs p)
 #pragma unroll
             for (int pz = 2; pz >= 0; --pz)
 #pragma unroll
-                for (int nt = 0; nt < NTH; ++nt)
-                    acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b[pz][nt], acc[nt], 0, 0, 0);
+                for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                    for (int nt = 0; nt < NTH; ++nt)
+                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[mt], b[pz][nt], acc[mt][nt], 0, 0, 0);
         }
         // into the fp64 sums after every 64 k (d is a multiple of 64)
         if (KB == 64 || (ks & 1) == 1 || ks + 1 == ksteps) {
 #pragma unroll
-            for (int nt = 0; nt < NTH; ++nt) {
+            for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                for (int v = 0; v < 4; ++v) sum[nt][v] += (double)acc[nt][v];
-                acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-            }
+                for (int nt = 0; nt < NTH; ++nt) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) sum[mt][nt][v] += (double)acc[mt][nt][v];
+                    acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+                }
         }
     }
     __syncthreads();                                    // every wave is done with the stages: reuse as logits
@@ -458,12 +470,14 @@ __global__ void __launch_bounds__(TG * 128) gate_tiled_kernel(GateArgs p)
         if (!tile_ok[nt]) continue;
         const int e = (eh * NTH + nt) * 16 + (lane & 15);
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int tok = tg * 16 + 4 * (lane >> 4) + v;
-            double s = sum[nt][v];
-            if (p.bias != nullptr && e < p.m) s += (double)p.bias[e];
-            logit[tok * p.m_pad + e] = (float)s;
-        }
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int tok = (tg + mt) * 16 + 4 * (lane >> 4) + v;
+                double s = sum[mt][nt][v];
+                if (p.bias != nullptr && e < p.m) s += (double)p.bias[e];
+                logit[tok * p.m_pad + e] = (float)s;
+            }
     }
     __syncthreads();
     if (p.K + 1 <= 16) {
@@ -775,25 +789,28 @@ hipError_t launch_route(const Dims& D, const bf16_t* x, const float* gate_w, con
             const int lds = std::max(g.n_stage * stage, 16 * tgw * D.m_pad * 4);
             const int blocks = ceil_div(D.T, 16 * tgw);
             hipError_t e = hipSuccess;
-#define BMOE_GATE_TILED(TG_, NTH_, KB_)                                                                          \
+#define BMOE_GATE_TILED(TG_, NTH_, KB_, MT_)                                                                         \
             do {                                                                                                   \
                 static bool attr_set = false;                                                                      \
                 if (!attr_set) {                                                                                   \
-                    e = hipFuncSetAttribute(reinterpret_cast<const void*>(gate_tiled_kernel<TG_, NTH_, KB_>),      \
+                    e = hipFuncSetAttribute(reinterpret_cast<const void*>(gate_tiled_kernel<TG_, NTH_, KB_, MT_>), \
                                             hipFuncAttributeMaxDynamicSharedMemorySize,                            \
                                             kGateLds - 1024);                                                      \
                     attr_set = e == hipSuccess;                                                                    \
                 }                                                                                                  \
-                if (e == hipSuccess) gate_tiled_kernel<TG_, NTH_, KB_><<<blocks, TG_ * 128, lds, s>>>(g);          \
+                if (e == hipSuccess) gate_tiled_kernel<TG_, NTH_, KB_, MT_><<<blocks, TG_ * 128, lds, s>>>(g);     \
             } while (0)
+            // more than 8 expert tiles (at most 16): two token tiles per wave and a quarter of the experts
+            // instead of one token tile and half of the experts
+            static_assert(kMaxExperts <= 256, "a wave holds at most four expert tiles per quarter");
             if (tgw == 4) {
-                if (half_tiles <= 2) { if (wide) BMOE_GATE_TILED(4, 2, 64); else BMOE_GATE_TILED(4, 2, 32); }
-                else if (half_tiles <= 4) { if (wide) BMOE_GATE_TILED(4, 4, 64); else BMOE_GATE_TILED(4, 4, 32); }
-                else BMOE_GATE_TILED(4, 8, 32);
+                if (half_tiles <= 2) { if (wide) BMOE_GATE_TILED(4, 2, 64, 1); else BMOE_GATE_TILED(4, 2, 32, 1); }
+                else if (half_tiles <= 4) { if (wide) BMOE_GATE_TILED(4, 4, 64, 1); else BMOE_GATE_TILED(4, 4, 32, 1); }
+                else BMOE_GATE_TILED(4, 4, 32, 2);
             } else {
-                if (half_tiles <= 2) { if (wide) BMOE_GATE_TILED(2, 2, 64); else BMOE_GATE_TILED(2, 2, 32); }
-                else if (half_tiles <= 4) { if (wide) BMOE_GATE_TILED(2, 4, 64); else BMOE_GATE_TILED(2, 4, 32); }
-                else BMOE_GATE_TILED(2, 8, 32);
+                if (half_tiles <= 2) { if (wide) BMOE_GATE_TILED(2, 2, 64, 1); else BMOE_GATE_TILED(2, 2, 32, 1); }
+                else if (half_tiles <= 4) { if (wide) BMOE_GATE_TILED(2, 4, 64, 1); else BMOE_GATE_TILED(2, 4, 32, 1); }
+                else BMOE_GATE_TILED(2, 4, 32, 2);
             }
 #undef BMOE_GATE_TILED
             if (e != hipSuccess) return e;
