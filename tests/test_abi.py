@@ -114,3 +114,29 @@ def test_build_united_validates():
     assert L.moe_build_united(C.byref(cfg), C.byref(w), C.byref(w), None, -1, None, None, 0, None) == -1
     # calibration requested but no workspace
     assert L.moe_build_united(C.byref(cfg), C.byref(w), C.byref(w), _fake(), 16, _fake(0x70000), None, 0, None) == -4
+
+
+def test_distill_workspace_and_validation_on_the_host():
+    """The distillation entry points reject bad arguments before any device work (dummy pointers)."""
+    L = P.lib()
+    cfg = P.make_config(256, 512, 8, 2, 4)
+    n = C.c_size_t(0)
+    assert L.moe_distill_workspace_size(C.byref(cfg), 128, C.byref(n)) == 0
+    assert n.value > P.workspace_size(cfg, 128) and n.value % 256 == 0
+    assert L.moe_distill_workspace_size(C.byref(cfg), 96, C.byref(n)) == -2       # not a multiple of 64
+    assert L.moe_distill_workspace_size(C.byref(cfg), 0, C.byref(n)) == -2
+    assert L.moe_distill_workspace_size(C.byref(cfg), 128, None) == -1
+    w = B.moe_ffn_weights(_fake(0x10000), _fake(0x20000), _fake(0x30000))
+
+    def distill(n_calib=128, steps=1, lr=1e-3, x=_fake(0x40000), ws=_fake(0x100000), nbytes=1 << 40, ex=C.byref(w)):
+        return L.moe_distill_united(C.byref(cfg), ex, C.byref(w), x, n_calib, steps, lr, None, ws, nbytes, None)
+
+    assert distill(n_calib=100) == -2
+    assert distill(steps=-1) == -1
+    assert distill(lr=-1.0) == -1
+    assert distill(lr=float("nan")) == -1
+    assert distill(x=None) == -1
+    assert distill(ex=None) == -1
+    assert distill(ws=None) == -4
+    assert distill(nbytes=1024) == -4
+    assert distill(ws=_fake(0x100010)) == -3                                      # workspace not 256-byte aligned
