@@ -136,8 +136,9 @@ def main():
         achieved = flops_gemm1 / (gemm1_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None}
-    # with 256-row tiles GEMM1 is three launches (the GEMM kernel, its K-split tail, the tail sum): all timed
-    roofline["kernel"] = "GEMM1 (ffn_gemm_*_kernel<SWIGLU> and, with 256-row tiles, its K-split tail)"
+    # with 256-row tiles GEMM1 is four launches (the GEMM kernel, then column halves, K slices and the sum of the
+    # K slices for the tiles left over after its last full round): all of them are inside the timed interval
+    roofline["kernel"] = "GEMM1 (ffn_gemm_*_kernel<SWIGLU> and, with 256-row tiles, the launches for its left-over tiles)"
     roofline["kernel_ms"] = gemm1_ms
     # HBM bytes of one GEMM1 launch as counted by rocprofv3 (FETCH_SIZE + WRITE_SIZE, scaled by a copy
     # probe): taken from the committed profile summary of this workload, if there is one
