@@ -739,52 +739,79 @@ __host__ __device__ inline bool tail_halves(int G, int rem, int nk_all)
     return rem > 0 && 2 * rem <= G && nk_all >= 8 && tail_split(G, rem, nk_all) == 1;
 }
 
+// What a block of the persistent kernel needs to know about the launch as a whole: computed once per block
+// (the divisions in it would otherwise be repeated for every tile).
+struct Sched {
+    int n_mt, tiles;
+    int chunk;                                  // whole tiles per XCD (MODE 0 without scratch: tiles x K slices per XCD)
+    int t_full, rem;                            // tiles in full rounds, tiles left over
+    int sl;                                     // K slices per left-over tile (1: not cut along K)
+    int halves;                                 // left-over tiles are cut in two along N
+};
+
+template <int MODE>
+__device__ __forceinline__ Sched make_sched(const GemmArgs& p, int slots)
+{
+    Sched sc;
+    sc.n_mt = p.table[0];
+    sc.tiles = sc.n_mt * p.n_ntiles;
+    if (MODE == 0 && p.partial == nullptr) {
+        sc.chunk = (sc.tiles * p.ksplit + 7) >> 3;
+        sc.t_full = sc.tiles; sc.rem = 0; sc.sl = 1; sc.halves = 0;
+    } else {
+        const int G = slots * 8;
+        sc.t_full = sc.tiles / G * G;
+        sc.chunk = sc.t_full >> 3;
+        sc.rem = sc.tiles - sc.t_full;
+        sc.sl = tail_split(G, sc.rem, p.K / 64);
+        sc.halves = tail_halves(G, sc.rem, p.K / 64) ? 1 : 0;
+    }
+    return sc;
+}
+
 // MODE 0: whole tiles (the main launch); 1: K slices of the left-over tiles; 2: column halves of them.
 template <int BNC, int MODE>
-__device__ __forceinline__ bool decode_tile_at(const GemmArgs& p, int xcd, int bi, int slots, Tile& t)
+__device__ __forceinline__ bool decode_tile_at(const GemmArgs& p, const Sched& sc, int xcd, int bi, int slots, Tile& t)
 {
-    const int n_mt = p.table[0];
-    const int tiles = n_mt * p.n_ntiles;
+    const int n_mt = sc.n_mt;
     int L;
     t.ks = p.ksplit;
     t.part = -1;
     t.kslice = 0;
     t.half = 0;
     if (MODE == 0 && p.partial == nullptr) {
-        const int total = tiles * p.ksplit;
-        const int chunk = (total + 7) >> 3;
-        if (bi >= chunk) return false;
-        const int Lfull = xcd * chunk + bi;
+        const int total = sc.tiles * p.ksplit;
+        if (bi >= sc.chunk) return false;
+        const int Lfull = xcd * sc.chunk + bi;
         if (Lfull >= total) return false;
-        t.kslice = Lfull / tiles;
-        L = Lfull - t.kslice * tiles;
+        if (p.ksplit > 1) {
+            t.kslice = Lfull / sc.tiles;
+            L = Lfull - t.kslice * sc.tiles;
+        } else {
+            L = Lfull;
+        }
     } else {
         // Whole tiles: every XCD sweeps its contiguous chunk (a multiple of its `slots` blocks), then one more
         // round for the tiles left over if they are not cut.  Cut tiles are the work of the other two
         // instantiations, launched next, one piece per block: K slices slice-major, so that the blocks of an
         // XCD work on the same slices of K; column halves side by side, so that they share the A rows in L2.
-        const int G = slots * 8;
-        const int t_full = tiles / G * G, chunk = t_full >> 3;
-        const int rem = tiles - t_full;
-        const int sl = tail_split(G, rem, p.K / 64);
-        const bool halves = tail_halves(G, rem, p.K / 64);
-        if (MODE == 0 && bi < chunk) {
-            L = xcd * chunk + bi;
+        if (MODE == 0 && bi < sc.chunk) {
+            L = xcd * sc.chunk + bi;
         } else {
-            const int round = MODE == 0 ? bi - chunk : bi;
+            const int round = MODE == 0 ? bi - sc.chunk : bi;
             if (round >= slots) return false;
             const int c = xcd * slots + round;
             if (MODE == 0) {
-                if (sl > 1 || halves || c >= rem) return false;
-                L = t_full + c;
+                if (sc.sl > 1 || sc.halves || c >= sc.rem) return false;
+                L = sc.t_full + c;
             } else if (MODE == 1) {
-                if (sl <= 1 || c >= rem * sl) return false;
-                const int pz = c / rem, j = c - pz * rem;
-                L = t_full + j;
-                t.kslice = pz; t.ks = sl; t.part = j * sl + pz;
+                if (sc.sl <= 1 || c >= sc.rem * sc.sl) return false;
+                const int pz = c / sc.rem, j = c - pz * sc.rem;
+                L = sc.t_full + j;
+                t.kslice = pz; t.ks = sc.sl; t.part = j * sc.sl + pz;
             } else {
-                if (!halves || c >= 2 * rem) return false;
-                L = t_full + (c >> 1);
+                if (!sc.halves || c >= 2 * sc.rem) return false;
+                L = sc.t_full + (c >> 1);
                 t.half = c & 1;
             }
         }
@@ -896,8 +923,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
 
     const int xcd = blockIdx.x & 7, slots = gridDim.x >> 3;
     int bi = blockIdx.x >> 3;
+    const Sched sc = make_sched<MODE>(p, slots);
     Tile t;
-    if (!decode_tile_at<BNC, MODE>(p, xcd, bi, slots, t)) return;
+    if (!decode_tile_at<BNC, MODE>(p, sc, xcd, bi, slots, t)) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);
     // wave tile: rows wm * 128 .., B-tile rows wn * TN ..  (column half h of a tile: the 64-row quarters 2h, 2h+1)
@@ -1003,7 +1031,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
         // the next output tile of this block, or this one again when there is none (its index load is
         // issued either way, so the number of loads in flight does not depend on it)
         Tile tn;
-        const bool has_next = decode_tile_at<BNC, MODE>(p, xcd, bi + slots, slots, tn);
+        const bool has_next = decode_tile_at<BNC, MODE>(p, sc, xcd, bi + slots, slots, tn);
         if (!has_next) tn = t;
         const int gnext = GATHER ? gather_rows(tn) : 0;
 
