@@ -108,6 +108,31 @@ def test_register_staged_kernel_for_wide_offsets(monkeypatch):
         assert rel_err(npf(out), want) <= OUT_TOL
 
 
+def test_workspace_reuse_and_side_stream():
+    """One workspace, sized for the larger batch, serves calls of different sizes on a caller's stream: what an
+    earlier call left in it (row lists, tile tables, partial tiles of the K-split tail) must not show."""
+    big, _ = SMALL["k_split_tail_gemm2"]
+    small = big.with_(T=300)
+    c_big, c_small = P.config_of(big), P.config_of(small)
+    Lb, Lgb = _layer(big, seed=1)
+    Ls, Lgs = _layer(small, seed=2)
+    united = tuple(a.to(DEV) for a in WL.make_random_united(big, 0, "cpu"))
+    fresh_big = P.moe_forward(c_big, Lgb.x, Lgb.gate_w, Lgb.gate_b, Lgb.experts, united, None, 0.0)
+    fresh_small = P.moe_forward(c_small, Lgs.x, Lgs.gate_w, Lgs.gate_b, Lgb.experts, united, None, 0.5)
+    torch.cuda.synchronize()
+    ws = P.alloc_workspace(c_big, big.T, DEV)
+    ws.fill_(0xA5)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        a = P.moe_forward(c_big, Lgb.x, Lgb.gate_w, Lgb.gate_b, Lgb.experts, united, None, 0.0, workspace=ws, stream=side)
+        b = P.moe_forward(c_small, Lgs.x, Lgs.gate_w, Lgs.gate_b, Lgb.experts, united, None, 0.5, workspace=ws, stream=side)
+        a2 = P.moe_forward(c_big, Lgb.x, Lgb.gate_w, Lgb.gate_b, Lgb.experts, united, None, 0.0, workspace=ws, stream=side)
+    side.synchronize()
+    assert torch.equal(a, fresh_big) and torch.equal(a2, fresh_big)
+    assert torch.equal(b, fresh_small)
+
+
 def test_empty_batch_is_rejected():
     cfg = WL.CONFIGS["tiny"]
     L, Lg = _layer(cfg)
