@@ -41,6 +41,8 @@ def main():
     ap.add_argument("--salc", action="store_true",
                     help="also run the SLO-aware latency controller over a synthetic burst trace (to stderr)")
     ap.add_argument("--salc-layers", type=int, default=24, help="MoE layers per serving iteration in --salc")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the step replayed from a captured HIP graph (to stderr)")
     ap.add_argument("--distill", action="store_true",
                     help="also train the united experts by distillation on synthetic calibration tokens and compare "
                          "the full-brownout layer output before and after (to stderr)")
@@ -158,6 +160,22 @@ def main():
         pr = P.profile_collect()
         P.profile_disable()
         log("  per-kernel ms (mean of 10): " + ", ".join(f"{k}={v[0]/max(1,v[1]):.4f}" for k, v in pr.items()))
+
+    if args.graph:
+        # the same step captured once and replayed: what a serving loop that cannot afford launch latency would do
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            step()
+        for _ in range(args.warmup):
+            g.replay()
+        torch.cuda.synchronize()
+        tg = time.perf_counter()
+        for _ in range(args.steps):
+            g.replay()
+        torch.cuda.synchronize()
+        log(f"  replayed from a HIP graph: {(time.perf_counter() - tg) * 1e3 / args.steps:.3f} ms per step "
+            f"(eager launches: {ms_per_step:.3f})")
 
     if args.sweep:
         # latency against the brownout threshold, 1.0 -> 0.0 in steps of 0.1, partial and full brownout

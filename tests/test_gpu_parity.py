@@ -133,6 +133,37 @@ def test_workspace_reuse_and_side_stream():
     assert torch.equal(b, fresh_small)
 
 
+@pytest.mark.parametrize("name", ["mid_tile", "k_split_tail_gemm2"])
+def test_forward_replays_from_a_hip_graph(name):
+    """moe_forward launches kernels only, so a caller can capture it; every replay, with eager work on other
+    inputs in between, must give the eager result for whatever the input buffer holds at that moment."""
+    cfg, _ = SMALL[name]
+    thr = 0.5
+    c = P.config_of(cfg)
+    L, Lg = _layer(cfg, seed=3)
+    _, Lg2 = _layer(cfg, seed=4)
+    united = tuple(a.to(DEV) for a in WL.make_random_united(cfg, 0, "cpu"))
+    x_buf = Lg.x.clone()
+    out_buf = torch.empty_like(x_buf)
+    ws = P.alloc_workspace(c, cfg.T, DEV)
+
+    def eager(x):
+        return P.moe_forward(c, x, Lg.gate_w, Lg.gate_b, Lg.experts, united, Lg.shared, thr)
+
+    want1, want2 = eager(Lg.x), eager(Lg2.x)           # also the warm-up: one-time attribute calls happen here
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        P.moe_forward(c, x_buf, Lg.gate_w, Lg.gate_b, Lg.experts, united, Lg.shared, thr, out=out_buf, workspace=ws)
+    for x_new, want in ((Lg.x, want1), (Lg2.x, want2), (Lg.x, want1)):
+        x_buf.copy_(x_new)
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_buf, want)
+        assert torch.equal(eager(Lg2.x), want2)        # eager work between the replays
+        torch.cuda.synchronize()
+
+
 def test_empty_batch_is_rejected():
     cfg = WL.CONFIGS["tiny"]
     L, Lg = _layer(cfg)
