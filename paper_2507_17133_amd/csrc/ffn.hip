@@ -16,8 +16,8 @@
 //
 // Kernels, by tile height (chosen on the host from the expected rows per unit):
 //   256 rows  ffn_gemm_w4_kernel   four waves, one per SIMD, 128x128 wave tiles, 16x16x32 MFMA, persistent;
-//                                  two more instantiations for the tiles left over after the last full round:
-//                                  cut along K (fp32 partial tiles, gemm_tail_sum_kernel) or in two along N
+//             ffn_gemm_w4_tail_kernel  the tiles left over after its last full round: cut along K (fp32
+//                                  partial tiles, summed by gemm_tail_sum_kernel) or in two along N
 //             ffn_gemm_rs_kernel   eight waves, register-staged; stand-in when A offsets exceed 32 bits
 //   128 rows  ffn_gemm_pp_kernel   eight waves in two groups that alternate memory and MFMA phases
 //   64, 32    ffn_gemm_kernel      four waves, plain multi-stage ring (decode: weight streaming bound)
@@ -896,7 +896,7 @@ __global__ void __launch_bounds__(256) gemm_tail_sum_kernel(GemmArgs p, int G)
 }
 
 template <bool SWIGLU, int MODE>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) ffn_gemm_w4_kernel(GemmArgs p)
+__device__ __forceinline__ void w4_block(const GemmArgs& p, const int block, const int n_blocks)
 {
     constexpr int BM = 256, BN = 256, BK = 64, NW = 4;
     using L = Lds<BK>;
@@ -921,8 +921,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
     static_assert(2 * ABUF + 3 * BBUF <= 160 * 1024, "LDS budget of one CU");
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
-    const int xcd = blockIdx.x & 7, slots = gridDim.x >> 3;
-    int bi = blockIdx.x >> 3;
+    const int xcd = block & 7, slots = n_blocks >> 3;
+    int bi = block >> 3;
     const Sched sc = make_sched<MODE>(p, slots);
     Tile t;
     if (!decode_tile_at<BNC, MODE>(p, sc, xcd, bi, slots, t)) return;
@@ -1148,6 +1148,24 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
 }
 
+// The main launch: whole tiles.
+template <bool SWIGLU>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) ffn_gemm_w4_kernel(GemmArgs p)
+{
+    w4_block<SWIGLU, 0>(p, blockIdx.x, gridDim.x);
+}
+
+// The launch for the left-over tiles, twice the grid of the main launch: its first half takes column halves,
+// its second half K slices.  A launch uses at most one of the two (only the device knows which), the blocks
+// of the other return at once; block id mod 8 is the XCD in both halves (the main grid is a multiple of 8).
+template <bool SWIGLU>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) ffn_gemm_w4_tail_kernel(GemmArgs p)
+{
+    const int g = gridDim.x >> 1;
+    if ((int)blockIdx.x < g) w4_block<SWIGLU, 2>(p, blockIdx.x, g);
+    else w4_block<SWIGLU, 1>(p, blockIdx.x - g, g);
+}
+
 // ------------------------------------------------------------------------------------------------
 // combine: one thread = 8 columns of one token; rows summed in slot order, shared experts first.
 // ------------------------------------------------------------------------------------------------
@@ -1260,16 +1278,13 @@ static hipError_t launch_w4(const GemmArgs& a, int max_mtiles, hipStream_t s)
     constexpr int LDS = 160 * 1024;
     static bool attr_set = false;
     static int n_cu = 0;
-    auto kern = ffn_gemm_w4_kernel<SWIGLU, 0>;
-    auto kern_tail = ffn_gemm_w4_kernel<SWIGLU, 1>;
-    auto kern_half = ffn_gemm_w4_kernel<SWIGLU, 2>;
+    auto kern = ffn_gemm_w4_kernel<SWIGLU>;
+    auto kern_tail = ffn_gemm_w4_tail_kernel<SWIGLU>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
         if (e != hipSuccess) return e;
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern_tail), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern_half), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
         if (e != hipSuccess) return e;
         int dev = 0;
         e = hipGetDevice(&dev);
@@ -1291,8 +1306,7 @@ static hipError_t launch_w4(const GemmArgs& a, int max_mtiles, hipStream_t s)
         // then summed) or in two along N; which it is, if any, only the tile table on the device knows
         const int max_tail = (int)std::min<long>(total, grid - 1);
         if (max_tail > 0) {
-            kern_half<<<grid, 256, LDS, s>>>(g);
-            kern_tail<<<grid, 256, LDS, s>>>(g);
+            kern_tail<<<2 * grid, 256, LDS, s>>>(g);
             gemm_tail_sum_kernel<SWIGLU><<<std::min(max_tail * 64, 2048), 256, 0, s>>>(g, grid);
         }
     }
