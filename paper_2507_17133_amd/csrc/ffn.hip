@@ -16,8 +16,9 @@
 //
 // Kernels, by tile height (chosen on the host from the expected rows per unit):
 //   256 rows  ffn_gemm_w4_kernel   four waves, one per SIMD, 128x128 wave tiles, 16x16x32 MFMA, persistent;
-//             ffn_gemm_w4_tail_kernel  the tiles left over after its last full round: cut along K (fp32
-//                                  partial tiles, summed by gemm_tail_sum_kernel) or in two along N
+//                                  further blocks of the same launch take the tiles left over after the last
+//                                  full round: cut along K (fp32 partial tiles, summed by
+//                                  gemm_tail_sum_kernel) or in two along N
 //             ffn_gemm_rs_kernel   eight waves, register-staged; stand-in when A offsets exceed 32 bits
 //   128 rows  ffn_gemm_pp_kernel   eight waves in two groups that alternate memory and MFMA phases
 //   64, 32    ffn_gemm_kernel      four waves, plain multi-stage ring (decode: weight streaming bound)
@@ -1148,22 +1149,19 @@ __device__ __forceinline__ void w4_block(const GemmArgs& p, const int block, con
     __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
 }
 
-// The main launch: whole tiles.
+// One launch: G blocks (one per CU) for the whole tiles and, where the left-over tiles may be cut (p.partial
+// set), 2 G more behind them: G for column halves, G for K slices.  They are independent work, so a CU
+// picks one up as soon as its block of whole tiles is done; a launch uses at most one of the two kinds
+// (only the device knows which), the blocks of the other return at once.  Block id mod 8 is the XCD in all
+// three ranges (G is a multiple of 8).
 template <bool SWIGLU>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) ffn_gemm_w4_kernel(GemmArgs p)
 {
-    w4_block<SWIGLU, 0>(p, blockIdx.x, gridDim.x);
-}
-
-// The launch for the left-over tiles, twice the grid of the main launch: its first half takes column halves,
-// its second half K slices.  A launch uses at most one of the two (only the device knows which), the blocks
-// of the other return at once; block id mod 8 is the XCD in both halves (the main grid is a multiple of 8).
-template <bool SWIGLU>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) ffn_gemm_w4_tail_kernel(GemmArgs p)
-{
-    const int g = gridDim.x >> 1;
-    if ((int)blockIdx.x < g) w4_block<SWIGLU, 2>(p, blockIdx.x, g);
-    else w4_block<SWIGLU, 1>(p, blockIdx.x - g, g);
+    const int g = p.partial != nullptr ? (int)gridDim.x / 3 : (int)gridDim.x;
+    const int b = blockIdx.x;
+    if (b < g) w4_block<SWIGLU, 0>(p, b, g);
+    else if (b < 2 * g) w4_block<SWIGLU, 2>(p, b - g, g);
+    else w4_block<SWIGLU, 1>(p, b - 2 * g, g);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1279,12 +1277,9 @@ static hipError_t launch_w4(const GemmArgs& a, int max_mtiles, hipStream_t s)
     static bool attr_set = false;
     static int n_cu = 0;
     auto kern = ffn_gemm_w4_kernel<SWIGLU>;
-    auto kern_tail = ffn_gemm_w4_tail_kernel<SWIGLU>;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-        if (e != hipSuccess) return e;
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern_tail), hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
         if (e != hipSuccess) return e;
         int dev = 0;
         e = hipGetDevice(&dev);
@@ -1300,16 +1295,11 @@ static hipError_t launch_w4(const GemmArgs& a, int max_mtiles, hipStream_t s)
     // number of blocks; fewer when there cannot be that many tiles
     const int grid = (int)std::min<long>((total + 7) / 8 * 8, std::max(8, n_cu / 8 * 8));
     if (g.ksplit != 1 || grid > g.partial_cap) g.partial = nullptr;
-    kern<<<grid, 256, LDS, s>>>(g);
-    if (g.partial) {
-        // the tiles left over after the last full round of `grid` tiles: cut along K (one slice per block,
-        // then summed) or in two along N; which it is, if any, only the tile table on the device knows
-        const int max_tail = (int)std::min<long>(total, grid - 1);
-        if (max_tail > 0) {
-            kern_tail<<<2 * grid, 256, LDS, s>>>(g);
-            gemm_tail_sum_kernel<SWIGLU><<<std::min(max_tail * 64, 2048), 256, 0, s>>>(g, grid);
-        }
-    }
+    // at most grid - 1 tiles are left over after the last full round of `grid` tiles
+    const int max_tail = (int)std::min<long>(total, grid - 1);
+    if (max_tail <= 0) g.partial = nullptr;
+    kern<<<g.partial ? 3 * grid : grid, 256, LDS, s>>>(g);
+    if (g.partial) gemm_tail_sum_kernel<SWIGLU><<<std::min(max_tail * 64, 2048), 256, 0, s>>>(g, grid);
     return hipGetLastError();
 }
 
