@@ -138,9 +138,9 @@ def main():
         achieved = flops_gemm1 / (gemm1_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None}
-    # with 256-row tiles GEMM1 is four launches (the GEMM kernel, then column halves, K slices and the sum of the
-    # K slices for the tiles left over after its last full round): all of them are inside the timed interval
-    roofline["kernel"] = "GEMM1 (ffn_gemm_*_kernel<SWIGLU> and, with 256-row tiles, the launches for its left-over tiles)"
+    # with 256-row tiles GEMM1 is two launches (the GEMM kernel, whose extra blocks take the pieces of the tiles
+    # left over after its last full round, and the sum of their K slices): both are inside the timed interval
+    roofline["kernel"] = "GEMM1 (ffn_gemm_*_kernel<SWIGLU> and, with 256-row tiles, gemm_tail_sum_kernel)"
     roofline["kernel_ms"] = gemm1_ms
     # HBM bytes of one GEMM1 launch as counted by rocprofv3 (FETCH_SIZE + WRITE_SIZE, scaled by a copy
     # probe): taken from the committed profile summary of this workload, if there is one
