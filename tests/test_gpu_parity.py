@@ -164,6 +164,27 @@ def test_forward_replays_from_a_hip_graph(name):
         torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("name", ["tiny", "many_experts", "tiled_gate_2groups"])
+def test_exact_ties_go_to_the_lower_expert_id(name):
+    """All-zero activations: every affinity is exactly equal, so TopK must list experts 0..K-1 for every token
+    (lower id wins, in all three gate kernels' paths), every token is flagged as a near tie, the weights are
+    1/K, and the layer output is zero (FFN(0) = 0)."""
+    cfg, _ = SMALL[name]
+    L, Lg = _layer(cfg)
+    c = P.config_of(cfg)
+    x0 = torch.zeros_like(Lg.x)
+    R = P.moe_route(c, x0, Lg.gate_w, None, 1.0)
+    out = P.moe_forward(c, x0, Lg.gate_w, None, Lg.experts, None, Lg.shared, 1.0)
+    torch.cuda.synchronize()
+    idx = npf(R.topk_idx)
+    assert (idx == np.arange(cfg.K)[None, :]).all()
+    assert np.allclose(npf(R.topk_w), 1.0 / cfg.K, rtol=1e-6)
+    assert (npf(R.near_tie) == 1).all() or cfg.K == cfg.m
+    cnt = npf(R.expert_cnt)
+    assert (cnt[:cfg.K] == cfg.T).all() and (cnt[cfg.K:] == 0).all()
+    assert (npf(out) == 0).all()
+
+
 def test_empty_batch_is_rejected():
     cfg = WL.CONFIGS["tiny"]
     L, Lg = _layer(cfg)
