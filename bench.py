@@ -41,6 +41,8 @@ def main():
     ap.add_argument("--salc", action="store_true",
                     help="also run the SLO-aware latency controller over a synthetic burst trace (to stderr)")
     ap.add_argument("--salc-layers", type=int, default=24, help="MoE layers per serving iteration in --salc")
+    ap.add_argument("--no-probes", action="store_true",
+                    help="skip the two ceiling probes (pure MFMA loop on this workload's weight bits, read-only sweep)")
     ap.add_argument("--graph", action="store_true",
                     help="also time the step replayed from a captured HIP graph (to stderr)")
     ap.add_argument("--distill", action="store_true",
@@ -255,6 +257,23 @@ def main():
             f"{args.distill_steps} Adam steps, lr {lr:.2e}): {dt:.2f} s = {dt/max(1,len(multi)*max(1,args.distill_steps))*1e3:.2f} ms per "
             f"group step; mean loss {h[multi,0].mean():.4g} -> {h[multi,-1].mean():.4g}; layer output error against "
             f"threshold 1 at threshold 0: parameter mean {rel(before):.4f}, distilled {rel(after):.4f}")
+
+    if not args.no_probes:
+        # What this machine sustains on the resource the dominant kernel is priced against, measured after the timed
+        # region: a pure MFMA loop whose operand bits are this workload's expert weights (random data draws
+        # more power than constants, and the chip clocks down under it), or a read-only sweep of the weights.
+        w1 = L.experts[0]
+        mfma_data = P.probe_mfma(w1)
+        mfma_const = P.probe_mfma(torch.ones(65536, dtype=torch.bfloat16, device=dev))
+        hbm_read = P.probe_hbm_read(w1)
+        measured = hbm_read if roofline["bound"] == "hbm" else mfma_data
+        roofline["measured_ceiling"] = measured
+        roofline["frac_of_measured_ceiling"] = roofline["achieved"] / measured
+        roofline["ceilings"] = {"mfma_loop_weight_bits_tflops": mfma_data, "mfma_loop_constant_bits_tflops": mfma_const,
+                                "hbm_read_gbs": hbm_read}
+        log(f"  measured ceilings on this box: pure MFMA loop {mfma_data:.0f} TFLOP/s on the weights' bits "
+            f"({mfma_const:.0f} on constants; nominal {PEAK_BF16_TFLOPS:.0f}), read-only sweep {hbm_read:.0f} GB/s "
+            f"(nominal {PEAK_HBM_GBS:.0f}); GEMM1 at {roofline['frac_of_measured_ceiling']:.3f} of its measured ceiling")
 
     cpu = None
     if not args.no_cpu_baseline:

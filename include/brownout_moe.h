@@ -199,6 +199,29 @@ moe_status moe_profile_enable(int32_t stage_mask);
 moe_status moe_profile_collect(double *total_ms /*[MOE_N_STAGES]*/, int64_t *launches /*[MOE_N_STAGES]*/);
 
 /*
+ * Measurement aids for benchmarks: what the GPU at hand sustains on the two
+ * resources the layer is priced against, so that a roofline fraction can be
+ * stated against the measured ceiling beside the nominal one.  Both calls launch
+ * on the caller's stream, time a batch of launches with HIP events after a
+ * warm-up (0.3 s and 0.1 s) and WAIT for the stream; they allocate nothing.
+ *   moe_probe_mfma      a loop of independent bf16 MFMAs (16x16x32, fp32
+ *                       accumulate) on register operands, eight waves per CU, no
+ *                       memory traffic.  The operand bits are the first 64 KiB of
+ *                       `operands` (device, bf16; operand_bytes >= 65536): pass
+ *                       real weights to see the rate under the power the data
+ *                       draws, constants to see the rate without that limit.
+ *                       sink: device scratch of >= 2 MiB.  Result: TFLOP/s.
+ *   moe_probe_hbm_read  every thread adds up 16-byte loads of buf (device,
+ *                       bytes >= 1 MiB, use a buffer far larger than the caches),
+ *                       grid-stride.  sink: device, >= 4 bytes.  Result: GB/s.
+ * Errors: NULL pointers (MOE_ERR_INVALID_ARG), buffers too small
+ * (MOE_ERR_WORKSPACE), misaligned pointers, HIP failures.
+ */
+moe_status moe_probe_mfma(const void *operands, size_t operand_bytes, void *sink, size_t sink_bytes, void *stream,
+                          double *tflops);
+moe_status moe_probe_hbm_read(const void *buf, size_t bytes, void *sink, size_t sink_bytes, void *stream, double *gbs);
+
+/*
  * SLO-aware latency control (the paper's Algorithm 2, "SLO-Aware Latency
  * Control Algorithm"): the host-side controller that moves `threshold`
  * between calls of moe_forward.  Pure host functions, no device work, no state.

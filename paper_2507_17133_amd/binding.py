@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libbrownout_moe.so")
 MOE_OK = 0
 STAGES = ("prep", "gate", "count", "scan", "scatter", "tiles", "gemm1", "gemm2", "combine")
 EXPORTS = ("moe_status_string", "moe_last_hip_error", "moe_workspace_size", "moe_build_united", "moe_route",
-           "moe_forward", "moe_distill_workspace_size", "moe_distill_united", "moe_profile_enable", "moe_profile_collect", "moe_latency_p90", "moe_salc_update")
+           "moe_forward", "moe_distill_workspace_size", "moe_distill_united", "moe_profile_enable", "moe_profile_collect", "moe_latency_p90", "moe_salc_update", "moe_probe_mfma", "moe_probe_hbm_read")
 
 
 class MoeError(RuntimeError):
@@ -85,6 +85,10 @@ def lib():
         L.moe_latency_p90.argtypes = [C.POINTER(C.c_double), C.c_size_t]
         L.moe_salc_update.restype = C.c_double
         L.moe_salc_update.argtypes = [C.c_double, C.c_double, C.POINTER(moe_salc_params)]
+        L.moe_probe_mfma.restype = C.c_int32
+        L.moe_probe_mfma.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_double)]
+        L.moe_probe_hbm_read.restype = C.c_int32
+        L.moe_probe_hbm_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_double)]
         L.moe_profile_enable.restype = C.c_int32
         L.moe_profile_enable.argtypes = [C.c_int32]
         L.moe_profile_collect.restype = C.c_int32
@@ -247,6 +251,26 @@ def moe_distill_united(cfg: moe_config, experts, united, calib_x: torch.Tensor, 
                                     _ptr(hist), _ptr(workspace), workspace.numel(), _stream(stream)),
            "moe_distill_united")
     return hist
+
+
+def probe_mfma(operands: torch.Tensor, stream=None) -> float:
+    """TFLOP/s of a pure bf16 MFMA loop whose operand bits are the first 64 KiB of `operands` (waits)."""
+    assert operands.is_cuda and operands.is_contiguous()
+    sink = torch.empty(2 << 20, dtype=torch.uint8, device=operands.device)
+    r = C.c_double(0.0)
+    _check(lib().moe_probe_mfma(_ptr(operands), operands.numel() * operands.element_size(), _ptr(sink), sink.numel(),
+                                _stream(stream), C.byref(r)), "moe_probe_mfma")
+    return r.value
+
+
+def probe_hbm_read(buf: torch.Tensor, stream=None) -> float:
+    """GB/s of a read-only sweep over `buf` (waits)."""
+    assert buf.is_cuda and buf.is_contiguous()
+    sink = torch.zeros(4, dtype=torch.uint8, device=buf.device)
+    r = C.c_double(0.0)
+    _check(lib().moe_probe_hbm_read(_ptr(buf), buf.numel() * buf.element_size(), _ptr(sink), sink.numel(),
+                                    _stream(stream), C.byref(r)), "moe_probe_hbm_read")
+    return r.value
 
 
 def profile_enable(stages: Sequence[str] = STAGES):

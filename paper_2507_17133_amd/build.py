@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libbrownout_moe.so")
-SOURCES = ["api.hip", "route.hip", "ffn.hip", "united.hip", "salc.hip", "distill.hip"]
+SOURCES = ["api.hip", "route.hip", "ffn.hip", "united.hip", "salc.hip", "distill.hip", "probe.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -508,6 +508,25 @@ moe_status moe_distill_united(const moe_config* cfg, const moe_ffn_weights* expe
     return MOE_OK;
 }
 
+moe_status moe_probe_mfma(const void* operands, size_t operand_bytes, void* sink, size_t sink_bytes, void* stream,
+                          double* tflops)
+{
+    if (!operands || !sink || !tflops) return MOE_ERR_INVALID_ARG;
+    if (operand_bytes < 65536 || sink_bytes < ((size_t)2 << 20)) return MOE_ERR_WORKSPACE;
+    if (misaligned(operands) || misaligned(sink)) return MOE_ERR_ALIGNMENT;
+    hipError_t e = probe_mfma(operands, sink, static_cast<hipStream_t>(stream), tflops);
+    return e == hipSuccess ? MOE_OK : hip_fail(e, "moe_probe_mfma");
+}
+
+moe_status moe_probe_hbm_read(const void* buf, size_t bytes, void* sink, size_t sink_bytes, void* stream, double* gbs)
+{
+    if (!buf || !sink || !gbs) return MOE_ERR_INVALID_ARG;
+    if (bytes < ((size_t)1 << 20) || sink_bytes < 4) return MOE_ERR_WORKSPACE;
+    if (misaligned(buf) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return MOE_ERR_ALIGNMENT;
+    hipError_t e = probe_hbm_read(buf, bytes, sink, static_cast<hipStream_t>(stream), gbs);
+    return e == hipSuccess ? MOE_OK : hip_fail(e, "moe_probe_hbm_read");
+}
+
 moe_status moe_profile_enable(int32_t stage_mask)
 {
     g_prof_mask = (unsigned)stage_mask & ((1u << MOE_N_STAGES) - 1u);

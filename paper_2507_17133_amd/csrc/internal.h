@@ -110,4 +110,9 @@ hipError_t launch_teacher_spread(const bf16_t* y_half, const float* tbar, size_t
 hipError_t distill_group(const bf16_t* x, int n, int d, int F, bf16_t* w1u, bf16_t* w3u, bf16_t* w2u, int steps,
                          float lr, float* hist, void* buf, hipStream_t s);
 
+// Probes (probe.hip): sustained rate of a pure MFMA loop on the caller's operand bits (operands: 64 KiB of
+// bf16, sink: 2 MiB), and of a read-only sweep over buf (sink: 4 bytes).  Both wait for the stream.
+hipError_t probe_mfma(const void* operands, void* sink, hipStream_t s, double* tflops);
+hipError_t probe_hbm_read(const void* buf, size_t bytes, void* sink, hipStream_t s, double* gbs);
+
 }  // namespace bmoe

@@ -140,3 +140,16 @@ def test_distill_workspace_and_validation_on_the_host():
     assert distill(ws=None) == -4
     assert distill(nbytes=1024) == -4
     assert distill(ws=_fake(0x100010)) == -3                                      # workspace not 256-byte aligned
+
+
+def test_probes_validate_on_the_host():
+    L = P.lib()
+    r = C.c_double(0.0)
+    assert L.moe_probe_mfma(None, 65536, _fake(), 2 << 20, None, C.byref(r)) == -1
+    assert L.moe_probe_mfma(_fake(), 65536, _fake(0x200000), 2 << 20, None, None) == -1
+    assert L.moe_probe_mfma(_fake(), 1024, _fake(0x200000), 2 << 20, None, C.byref(r)) == -4
+    assert L.moe_probe_mfma(_fake(), 65536, _fake(0x200000), 1024, None, C.byref(r)) == -4
+    assert L.moe_probe_mfma(_fake(0x10004), 65536, _fake(0x200000), 2 << 20, None, C.byref(r)) == -3
+    assert L.moe_probe_hbm_read(None, 1 << 30, _fake(), 4, None, C.byref(r)) == -1
+    assert L.moe_probe_hbm_read(_fake(), 1024, _fake(0x200000), 4, None, C.byref(r)) == -4
+    assert L.moe_probe_hbm_read(_fake(), 1 << 30, _fake(0x200000), 0, None, C.byref(r)) == -4

@@ -185,6 +185,19 @@ def test_exact_ties_go_to_the_lower_expert_id(name):
     assert (npf(out) == 0).all()
 
 
+def test_ceiling_probes_give_plausible_rates():
+    """The two measurement aids: a pure MFMA loop cannot beat the chip's nominal 2.5 PFLOP/s and constant
+    operand bits are never slower than random ones; a read-only sweep cannot beat 8 TB/s."""
+    torch.cuda.set_device(0)
+    rnd = torch.randn(1 << 16, device=DEV).to(torch.bfloat16)
+    t_rnd = P.probe_mfma(rnd)
+    t_one = P.probe_mfma(torch.ones(1 << 16, dtype=torch.bfloat16, device=DEV))
+    assert 200.0 < t_rnd <= 2600.0 and 200.0 < t_one <= 2600.0
+    assert t_one >= 0.95 * t_rnd
+    gbs = P.probe_hbm_read(torch.ones(1 << 30, dtype=torch.uint8, device=DEV))
+    assert 1000.0 < gbs <= 8200.0
+
+
 def test_empty_batch_is_rejected():
     cfg = WL.CONFIGS["tiny"]
     L, Lg = _layer(cfg)
