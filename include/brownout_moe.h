@@ -24,7 +24,13 @@
  *     N_s = n_shared, U = m + G + N_s execution units, numbered
  *     0..m-1 original experts, m..m+G-1 united experts, m+G.. shared experts.
  *   - Limits: d and F (and d_ff_shared) multiples of 64; m <= 256; K <= min(m,32);
- *     N_s <= 8; T*(K+N_s) <= 2^30.
+ *     N_s <= 8; T*(K+N_s) <= 2^30; T*d < 2^31 (MOE_ERR_UNSUPPORTED beyond).
+ *   - Per-device set-up (kernel attributes, device queries) happens in moe_init, in
+ *     moe_workspace_size, or else in the first call that launches work on that device.
+ *     Only the last cannot happen under stream capture: a caller that captures its very
+ *     first call into a HIP graph calls moe_init (or moe_workspace_size) beforehand.
+ *   - The environment variables BROWNOUT_MOE_BM / _GM / _KSPLIT (measurement switches,
+ *     unset in normal use) are read once, when the library first needs them.
  */
 #ifndef BROWNOUT_MOE_H
 #define BROWNOUT_MOE_H
@@ -57,8 +63,10 @@ typedef struct moe_config {
     int32_t score_fn;     /* 0: g = softmax over the K winners (the g equation);            */
                           /* 1: sigmoid(s) renormalised over the K winners                  */
     int32_t add_residual; /* 1: output includes the "x_t +" term of the layer equation      */
-    int32_t reserved;     /* must be 0                                                      */
+    int32_t gate_format;  /* what gate_w points to: MOE_GATE_FP32 (0) or MOE_GATE_PACKED (1)        */
 } moe_config;
+#define MOE_GATE_FP32 0   /* gate_w: [m][d] fp32, row i = centroid e_i                          */
+#define MOE_GATE_PACKED 1 /* gate_w: the buffer moe_pack_gate wrote from such a matrix          */
 
 /* n SwiGLU experts, FFN(x) = W2 (silu(W1 x) * (W3 x)):
  *   w1, w3: [n][F][d] bf16     w2: [n][d][F] bf16
@@ -66,6 +74,10 @@ typedef struct moe_config {
 typedef struct moe_ffn_weights {
     const void *w1, *w3, *w2;
 } moe_ffn_weights;
+/* The same three tensors where a call WRITES them (united experts being built or trained). */
+typedef struct moe_ffn_weights_out {
+    void *w1, *w3, *w2;
+} moe_ffn_weights_out;
 
 /* Routing artefacts.  In moe_route every field may be NULL (not wanted).  A
  * moe_route_out handed to moe_forward must have expert_unit, unit_cnt,
@@ -96,9 +108,32 @@ const char *moe_status_string(moe_status s);
 /* Text of the last HIP error seen by this thread ("" if none). */
 const char *moe_last_hip_error(void);
 
+/* Per-device set-up for the current HIP device (see Conventions).  Idempotent, thread-safe.
+ * Errors: MOE_ERR_HIP (no device, or a runtime call failed). */
+moe_status moe_init(void);
+
 /* Bytes of device workspace moe_route / moe_forward / moe_build_united need for up
- * to T_max tokens (or calibration tokens) with this config.  256-byte aligned base. */
+ * to T_max tokens (or calibration tokens) with this config: a workspace of this size
+ * serves every call with the same config and T <= T_max (the size never shrinks as
+ * T_max grows).  256-byte aligned base.  Also performs moe_init's set-up when a
+ * device is present. */
 moe_status moe_workspace_size(const moe_config *cfg, int32_t T_max, size_t *bytes);
+
+/*
+ * One-time repack of the gate matrix (section "Architecture of BrownoutMoE": the
+ * centroids e_i of the affinity s_{i,t} = x_t . e_i).  The gate runs on the bf16
+ * matrix cores with every fp32 weight cut into three bf16 pieces (hi + mid + lo
+ * carry its 24-bit significand, so x . e_i keeps fp32 accuracy).  With
+ * cfg->gate_format == MOE_GATE_FP32 moe_route / moe_forward cut gate_w on every
+ * call; a caller whose gate does not change between calls does it once here and
+ * passes `packed` as gate_w with cfg->gate_format == MOE_GATE_PACKED.  Results are
+ * bit-identical either way.
+ *   gate_w [m][d] fp32 (device)    packed: moe_gate_packed_size bytes (device)
+ * Errors: NULL / misaligned pointers, packed_bytes too small (MOE_ERR_WORKSPACE).
+ */
+moe_status moe_gate_packed_size(const moe_config *cfg, size_t *bytes);
+moe_status moe_pack_gate(const moe_config *cfg, const float *gate_w, void *packed, size_t packed_bytes,
+                         void *stream);
 
 /*
  * United experts (section "United Expert Model").  The paper trains one student
@@ -114,7 +149,7 @@ moe_status moe_workspace_size(const moe_config *cfg, int32_t T_max, size_t *byte
  * Errors: NULL experts/united pointers, n_calib < 0, workspace too small.
  */
 moe_status moe_build_united(const moe_config *cfg, const moe_ffn_weights *experts,
-                            const moe_ffn_weights *united_out, const void *calib_x, int32_t n_calib,
+                            const moe_ffn_weights_out *united_out, const void *calib_x, int32_t n_calib,
                             float *loss_per_group, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
@@ -134,13 +169,14 @@ moe_status moe_build_united(const moe_config *cfg, const moe_ffn_weights *expert
  * steps < 0, lr < 0 or NaN, workspace too small.
  */
 moe_status moe_distill_workspace_size(const moe_config *cfg, int32_t n_calib, size_t *bytes);
-moe_status moe_distill_united(const moe_config *cfg, const moe_ffn_weights *experts, const moe_ffn_weights *united,
+moe_status moe_distill_united(const moe_config *cfg, const moe_ffn_weights *experts, const moe_ffn_weights_out *united,
                               const void *calib_x, int32_t n_calib, int32_t steps, float lr, float *loss_history,
                               void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Gate + TopK + Algorithm 1 + row lists for T tokens x [T][d] bf16.
- *   gate_w [m][d] fp32 (row i = centroid e_i), gate_bias [m] fp32 or NULL:
+ *   gate_w [m][d] fp32 (row i = centroid e_i) or, with cfg->gate_format ==
+ *   MOE_GATE_PACKED, the buffer moe_pack_gate wrote; gate_bias [m] fp32 or NULL:
  *   s_{i,t} = x_t . e_i (+ bias_i), accumulated to fp32 accuracy.
  *   threshold in [0,1]: share of token->expert assignments that stays on
  *   original experts (1 = zero-brownout).  Algorithm 1 is read so that it
@@ -152,7 +188,7 @@ moe_status moe_distill_united(const moe_config *cfg, const moe_ffn_weights *expe
  * Errors: threshold outside [0,1] or NaN, top_k > n_experts, way < 1, T <= 0,
  * NULL x / gate_w / out, misaligned pointers, workspace too small.
  */
-moe_status moe_route(const moe_config *cfg, const void *x, int32_t T, const float *gate_w,
+moe_status moe_route(const moe_config *cfg, const void *x, int32_t T, const void *gate_w,
                      const float *gate_bias, double threshold, int32_t use_full_brownout,
                      const moe_route_out *out, void *workspace, size_t workspace_bytes, void *stream);
 
@@ -167,7 +203,7 @@ moe_status moe_route(const moe_config *cfg, const void *x, int32_t T, const floa
  * Intermediate activations are bf16, sums fp32; the sum over a token's rows
  * is taken in TopK order, shared experts first (deterministic, no atomics).
  */
-moe_status moe_forward(const moe_config *cfg, const void *x, int32_t T, const float *gate_w,
+moe_status moe_forward(const moe_config *cfg, const void *x, int32_t T, const void *gate_w,
                        const float *gate_bias, const moe_ffn_weights *experts, const moe_ffn_weights *united,
                        const moe_ffn_weights *shared, double threshold, int32_t use_full_brownout,
                        const moe_route_out *route, void *out, void *workspace, size_t workspace_bytes,

@@ -224,22 +224,38 @@ def forward_tokens_lazy(x_rows, topk_idx_rows, topk_w_rows, unit, m, get_weights
     """The layer equation for a few tokens when the weights are too large to hold as one float
     array: x_rows [n,d], topk_idx_rows / topk_w_rows [n,K] are the sampled tokens' data and
     get_weights(kind, index) returns one FFN's (w1 [F,d], w3 [F,d], w2 [d,F]) as float arrays,
-    kind in {"expert", "united", "shared"}.  Each term is one call of ffn() on one row; the sum
-    over terms is taken in double.  Returns [n,d] double."""
+    kind in {"expert", "united", "shared"}.  Every term FFN(x_t) of the equation is evaluated by
+    ffn() (one call per distinct FFN, on the rows of all sampled tokens that have a term in it:
+    rows are independent there, and the call spreads them over the host cores); the terms of a
+    token are then added in double in the equation's order: residual, shared experts, the TopK
+    entries in order (dropped experts contribute nothing).  Returns [n,d] double."""
     x_rows = _f32(x_rows)
     n, d = x_rows.shape
     K = topk_idx_rows.shape[1]
-    out = np.zeros((n, d), np.float64)
+    # which sampled tokens have a term in which FFN: (kind, index) -> [(token q, slot)]
+    terms = {}
     for q in range(n):
-        xr = x_rows[q:q + 1]
-        if add_residual:
-            out[q] += xr[0].astype(np.float64)
         for s in range(n_shared):
-            out[q] += ffn(xr, *get_weights("shared", s))[0]
+            terms.setdefault(("shared", s), []).append((q, s))
         for j in range(K):
             u = int(unit[int(topk_idx_rows[q, j])])
             if u < 0:
                 continue
-            w = get_weights("expert", u) if u < m else get_weights("united", u - m)
-            out[q] += float(topk_w_rows[q, j]) * ffn(xr, *w)[0]
+            key = ("expert", u) if u < m else ("united", u - m)
+            terms.setdefault(key, []).append((q, n_shared + j))
+    term_y = {}
+    for key, lst in terms.items():
+        qs = np.array([q for q, _ in lst], np.int64)
+        y = ffn(x_rows[qs], *get_weights(*key))
+        for i, (q, slot) in enumerate(lst):
+            term_y[(q, slot)] = y[i]
+    out = np.zeros((n, d), np.float64)
+    for q in range(n):
+        if add_residual:
+            out[q] += x_rows[q].astype(np.float64)
+        for s in range(n_shared):
+            out[q] += term_y[(q, s)]
+        for j in range(K):
+            if (q, n_shared + j) in term_y:
+                out[q] += float(topk_w_rows[q, j]) * term_y[(q, n_shared + j)]
     return out

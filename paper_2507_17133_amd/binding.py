@@ -19,8 +19,11 @@ LIB_PATH = os.path.join(_HERE, "libbrownout_moe.so")
 
 MOE_OK = 0
 STAGES = ("prep", "gate", "count", "scan", "scatter", "tiles", "gemm1", "gemm2", "combine")
-EXPORTS = ("moe_status_string", "moe_last_hip_error", "moe_workspace_size", "moe_build_united", "moe_route",
-           "moe_forward", "moe_distill_workspace_size", "moe_distill_united", "moe_profile_enable", "moe_profile_collect", "moe_latency_p90", "moe_salc_update", "moe_probe_mfma", "moe_probe_hbm_read")
+EXPORTS = ("moe_status_string", "moe_last_hip_error", "moe_init", "moe_workspace_size", "moe_gate_packed_size",
+           "moe_pack_gate", "moe_build_united", "moe_route", "moe_forward",
+           "moe_distill_workspace_size", "moe_distill_united", "moe_profile_enable", "moe_profile_collect",
+           "moe_latency_p90", "moe_salc_update", "moe_probe_mfma", "moe_probe_hbm_read")
+MOE_GATE_FP32, MOE_GATE_PACKED = 0, 1
 
 
 class MoeError(RuntimeError):
@@ -35,11 +38,14 @@ class moe_salc_params(C.Structure):
 
 class moe_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("d_model", "d_ff", "n_experts", "top_k", "way", "n_shared", "d_ff_shared",
-                                         "score_fn", "add_residual", "reserved")]
+                                         "score_fn", "add_residual", "gate_format")]
 
 
 class moe_ffn_weights(C.Structure):
     _fields_ = [("w1", C.c_void_p), ("w3", C.c_void_p), ("w2", C.c_void_p)]
+
+
+moe_ffn_weights_out = moe_ffn_weights        # same layout; the C header's type for tensors a call writes
 
 
 class moe_route_out(C.Structure):
@@ -62,8 +68,14 @@ def lib():
         L.moe_status_string.restype = C.c_char_p
         L.moe_status_string.argtypes = [C.c_int32]
         L.moe_last_hip_error.restype = C.c_char_p
+        L.moe_init.restype = C.c_int32
+        L.moe_init.argtypes = []
         L.moe_workspace_size.restype = C.c_int32
         L.moe_workspace_size.argtypes = [C.POINTER(moe_config), C.c_int32, C.POINTER(C.c_size_t)]
+        L.moe_gate_packed_size.restype = C.c_int32
+        L.moe_gate_packed_size.argtypes = [C.POINTER(moe_config), C.POINTER(C.c_size_t)]
+        L.moe_pack_gate.restype = C.c_int32
+        L.moe_pack_gate.argtypes = [C.POINTER(moe_config), C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.moe_build_united.restype = C.c_int32
         L.moe_build_united.argtypes = [C.POINTER(moe_config), C.POINTER(moe_ffn_weights), C.POINTER(moe_ffn_weights),
                                        C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
@@ -105,8 +117,33 @@ def _check(status: int, where: str):
         raise MoeError(status, where, detail + (": " + hip if hip else ""))
 
 
-def make_config(d_model, d_ff, n_experts, top_k, way, n_shared=0, d_ff_shared=0, score_fn=0, add_residual=0):
-    return moe_config(d_model, d_ff, n_experts, top_k, way, n_shared, d_ff_shared, score_fn, add_residual, 0)
+def make_config(d_model, d_ff, n_experts, top_k, way, n_shared=0, d_ff_shared=0, score_fn=0, add_residual=0,
+                gate_format=MOE_GATE_FP32):
+    return moe_config(d_model, d_ff, n_experts, top_k, way, n_shared, d_ff_shared, score_fn, add_residual, gate_format)
+
+
+def with_packed_gate(cfg: moe_config) -> moe_config:
+    """A copy of cfg that says gate_w is the buffer pack_gate() returned."""
+    c = moe_config.from_buffer_copy(cfg)
+    c.gate_format = MOE_GATE_PACKED
+    return c
+
+
+def init():
+    """Per-device set-up of the library on the current device (needed only before a FIRST call under capture)."""
+    _check(lib().moe_init(), "moe_init")
+
+
+def pack_gate(cfg: moe_config, gate_w: torch.Tensor, stream=None) -> torch.Tensor:
+    """One-time repack of the fp32 gate matrix [m][d]; pass the result as gate_w with with_packed_gate(cfg)."""
+    assert gate_w.is_cuda and gate_w.dtype == torch.float32 and gate_w.is_contiguous()
+    assert tuple(gate_w.shape) == (cfg.n_experts, cfg.d_model)
+    n = C.c_size_t(0)
+    _check(lib().moe_gate_packed_size(C.byref(cfg), C.byref(n)), "moe_gate_packed_size")
+    packed = torch.empty(n.value, dtype=torch.uint8, device=gate_w.device)
+    _check(lib().moe_pack_gate(C.byref(cfg), _ptr(gate_w), _ptr(packed), packed.numel(), _stream(stream)),
+           "moe_pack_gate")
+    return packed
 
 
 def config_of(cfg) -> moe_config:
@@ -180,7 +217,7 @@ def moe_route(cfg: moe_config, x, gate_w, gate_bias, threshold: float, use_full_
               out: Optional[RouteOut] = None, workspace: Optional[torch.Tensor] = None, stream=None) -> RouteOut:
     T = x.shape[0]
     assert x.is_cuda and x.dtype == torch.bfloat16 and x.is_contiguous() and x.shape[1] == cfg.d_model
-    assert gate_w.dtype == torch.float32 and gate_w.is_contiguous() and tuple(gate_w.shape) == (cfg.n_experts, cfg.d_model)
+    _check_gate(cfg, gate_w)
     if out is None:
         out = alloc_route_out(cfg, T, x.device)
     if workspace is None:
@@ -190,6 +227,14 @@ def moe_route(cfg: moe_config, x, gate_w, gate_bias, threshold: float, use_full_
                            1 if use_full_brownout else 0, C.byref(st), _ptr(workspace), workspace.numel(),
                            _stream(stream)), "moe_route")
     return out
+
+
+def _check_gate(cfg: moe_config, gate_w):
+    assert gate_w.is_cuda and gate_w.is_contiguous()
+    if cfg.gate_format == MOE_GATE_PACKED:
+        assert gate_w.dtype == torch.uint8
+    else:
+        assert gate_w.dtype == torch.float32 and tuple(gate_w.shape) == (cfg.n_experts, cfg.d_model)
 
 
 def moe_forward(cfg: moe_config, x, gate_w, gate_bias, experts, united=None, shared=None, threshold: float = 1.0,

@@ -1,14 +1,63 @@
 // C ABI of libbrownout_moe.so: argument validation, workspace carving, kernel sequencing, profiling.
 #include "internal.h"
+#include "tiles.h"
 
 #include <algorithm>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
 namespace bmoe {
+
+constexpr int kMixedRows = 384;      // expected rows per unit from which 256-row tiles are used
+constexpr int kMaxDevices = 64;
+
+static Tuning read_tuning()
+{
+    Tuning t{0, 4, 0};
+    if (const char* e = std::getenv("BROWNOUT_MOE_BM")) {
+        const int v = std::atoi(e);
+        if (v == 32 || v == 64 || v == 128 || v == 256) t.force_bm = v;
+    }
+    if (const char* e = std::getenv("BROWNOUT_MOE_GM")) t.group_m = std::max(1, std::min(64, std::atoi(e)));
+    if (const char* e = std::getenv("BROWNOUT_MOE_KSPLIT")) {
+        const int v = std::atoi(e);
+        if (v == 1 || v == 2 || v == 4) t.force_ksplit = v;
+    }
+    return t;
+}
+const Tuning& tuning()
+{
+    static const Tuning t = read_tuning();       // read once, when first asked for
+    return t;
+}
+
+static std::mutex g_init_mutex;
+static bool g_init_done[kMaxDevices] = {false};
+static DeviceInfo g_dev_info[kMaxDevices];
+
+hipError_t ensure_device_init(DeviceInfo* info)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_init_mutex);
+    if (!g_init_done[dev]) {
+        (void)tuning();
+        if ((e = init_ffn_kernels()) != hipSuccess) return e;
+        if ((e = init_route_kernels()) != hipSuccess) return e;
+        int n_cu = 0;
+        if ((e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+        g_dev_info[dev].n_cu = n_cu;
+        g_init_done[dev] = true;
+    }
+    if (info) *info = g_dev_info[dev];
+    return hipSuccess;
+}
 
 static thread_local std::string g_hip_error;
 
@@ -17,6 +66,25 @@ static moe_status hip_fail(hipError_t e, const char* where)
     g_hip_error = std::string(where) + ": " + hipGetErrorString(e);
     (void)hipGetLastError();
     return MOE_ERR_HIP;
+}
+
+// GEMM tile height from the expected rows per expert when every unit gets the same height.
+static int pick_tile_rows(int64_t expected_rows_per_unit)
+{
+    if (tuning().force_bm) return tuning().force_bm;
+    if (expected_rows_per_unit >= kMixedRows) return 256;
+    // one tile should hold an expert's rows with room for the spread around the mean: a second, nearly
+    // empty tile would stream the expert's weights a second time
+    if (expected_rows_per_unit >= 48) return 128;
+    if (expected_rows_per_unit >= 24) return 64;
+    return 32;
+}
+
+TilePlan make_tile_plan(int64_t expected_rows_per_unit)
+{
+    TilePlan p;
+    p.bm = pick_tile_rows(expected_rows_per_unit);
+    return p;
 }
 
 Dims make_dims(const moe_config& c, int T)
@@ -30,6 +98,7 @@ Dims make_dims(const moe_config& c, int T)
     D.m_pad = ceil_div(D.m, 16) * 16;
     D.Fmax = D.F > D.Fs ? D.F : D.Fs;
     D.score_fn = c.score_fn; D.add_residual = c.add_residual;
+    D.gate_format = c.gate_format;
     D.row_cap = (int64_t)T * D.slots;
     D.n_seg = ceil_div(T, kSegTokens);
     D.tile_cap = (int)(D.row_cap / kMinTileRows) + D.U;
@@ -40,7 +109,7 @@ Dims make_dims(const moe_config& c, int T)
     int ks = 1;
     while (ks < 4 && tiles2 * ks < 1024 && (D.F / 64) / (ks * 2) >= 8) ks *= 2;
     if (bm == 256) ks = 1;                                // the persistent kernel balances its tail itself
-    if (const char* e = std::getenv("BROWNOUT_MOE_KSPLIT")) ks = std::max(1, std::min(8, std::atoi(e)));
+    if (tuning().force_ksplit) ks = tuning().force_ksplit;
     D.ksplit = ks;
     D.y_plane = D.row_cap * (int64_t)D.d;
     const int64_t max_tiles = (D.row_cap / 256 + D.U) * (int64_t)std::max(ceil_div(D.d, 256), ceil_div(D.Fmax, 128));
@@ -48,24 +117,25 @@ Dims make_dims(const moe_config& c, int T)
     return D;
 }
 
-int pick_tile_rows(int64_t expected_rows_per_unit)
+// Rows of Y the workspace holds: an upper bound of rows x K planes over every batch of at most T tokens, so
+// that a workspace sized for T_max serves every smaller batch.  More than one plane is only chosen while
+// GEMM2 has few tiles (make_dims): 2 planes need fewer than 1024 tiles of at most 128 rows, 4 planes fewer
+// than 512, which bounds the rows such a batch can have.
+static int64_t y_rows_bound(const Dims& D)
 {
-    if (const char* e = std::getenv("BROWNOUT_MOE_BM")) {
-        const int v = std::atoi(e);
-        if (v == 32 || v == 64 || v == 128 || v == 256) return v;
-    }
-    if (expected_rows_per_unit >= 384) return 256;
-    // one tile should hold an expert's rows with room for the spread around the mean: a second, nearly
-    // empty tile would stream the expert's weights a second time
-    if (expected_rows_per_unit >= 48) return 128;
-    if (expected_rows_per_unit >= 24) return 64;
-    return 32;
+    const int64_t nt_d = ceil_div(D.d, 256);
+    const int64_t lim2 = 128 * (1024 / nt_d) + 128, lim4 = 128 * (512 / nt_d) + 128;
+    int64_t rows = std::max<int64_t>(D.row_cap, 2 * (int64_t)D.T);
+    rows = std::max(rows, 2 * std::min(D.row_cap, lim2));
+    rows = std::max(rows, 4 * std::min(D.row_cap, lim4));
+    if (tuning().force_ksplit) rows = std::max(rows, D.row_cap * tuning().force_ksplit);
+    return rows;
 }
 
-Workspace carve_workspace(const Dims& D)
+// Every piece grows (weakly) with T, so the total does: moe_workspace_size(T_max) covers every T <= T_max.
+// The routing pieces come first: they are all that routing alone needs.
+static void carve_route_pieces(const Dims& D, Workspace& W, size_t& o)
 {
-    Workspace W;
-    size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
     W.topk_idx = take((size_t)D.T * D.K * 4);
     W.topk_w = take((size_t)D.T * D.K * 4);
@@ -79,21 +149,32 @@ Workspace carve_workspace(const Dims& D)
     W.token_rows = take((size_t)D.row_cap * 4);
     W.n_rows = take(4);
     W.near_tie = take((size_t)D.T);
-    W.gate_split = take((size_t)3 * D.m_pad * D.d * 2);
+    W.gate_split = take(D.gate_format == MOE_GATE_PACKED ? 0 : (size_t)3 * D.m_pad * D.d * 2);
     W.seg_cnt = take((size_t)D.n_seg * D.U * 4);
     W.seg_off = take((size_t)D.n_seg * D.U * 4);
+    W.gate_hist = take((size_t)ceil_div(std::min(D.T, kSmallRouteTokens), 16) * D.m_pad * 4);
+}
+
+Workspace carve_workspace(const Dims& D)
+{
+    Workspace W;
+    size_t o = 0;
+    carve_route_pieces(D, W, o);
+    W.route_total = o;
+    auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
     W.tiles0 = take(16 + (size_t)D.tile_cap * 16);
     W.tiles1 = take(16 + (size_t)D.tile_cap * 16);
     W.h_rows = D.row_cap;
-    W.y_rows = D.row_cap * D.ksplit > 2 * (int64_t)D.T ? D.row_cap * D.ksplit : 2 * (int64_t)D.T;
+    W.y_rows = y_rows_bound(D);
     // one tile of rows past the end: GEMM2's ragged last tile reads (and discards) whole tiles of H
     W.H = take((size_t)(W.h_rows + 256) * D.Fmax * 2);
     W.Y = take((size_t)W.y_rows * D.d * 2);
     W.ones = take((size_t)D.T * 4);
-    // K-split tail of the persistent 256-row GEMMs: one fp32 tile per block of their grid
+    // K-split tail of the persistent 256-row GEMMs: one fp32 tile per block of their grid.  256-row tiles can
+    // occur from kMixedRows tokens on (a shared expert, or one unit holding all calibration tokens).
     W.partial = 0;
     W.partial_bytes = 0;
-    if (D.ksplit == 1 && pick_tile_rows(D.T) == 256) {
+    if (D.T >= kMixedRows || tuning().force_bm == 256) {
         W.partial_bytes = (size_t)D.tail_blocks * 256 * 256 * 4;
         W.partial = take(W.partial_bytes);
     }
@@ -104,7 +185,7 @@ Workspace carve_workspace(const Dims& D)
 static moe_status check_config(const moe_config* c)
 {
     if (!c) return MOE_ERR_INVALID_ARG;
-    if (c->reserved != 0) return MOE_ERR_INVALID_ARG;
+    if (c->gate_format != MOE_GATE_FP32 && c->gate_format != MOE_GATE_PACKED) return MOE_ERR_INVALID_ARG;
     if (c->n_experts < 1 || c->top_k < 1 || c->way < 1 || c->n_shared < 0) return MOE_ERR_INVALID_ARG;
     if (c->top_k > c->n_experts) return MOE_ERR_INVALID_ARG;
     if (c->score_fn != 0 && c->score_fn != 1) return MOE_ERR_INVALID_ARG;
@@ -119,6 +200,8 @@ static moe_status check_T(const moe_config* c, int32_t T)
 {
     if (T <= 0) return MOE_ERR_INVALID_ARG;
     if ((int64_t)T * (c->top_k + c->n_shared) > ((int64_t)1 << 30)) return MOE_ERR_SHAPE;
+    // byte offsets into the activations are 32-bit in the 256-row GEMM
+    if ((int64_t)T * c->d_model * 2 >= ((int64_t)1 << 32)) return MOE_ERR_UNSUPPORTED;
     return MOE_OK;
 }
 
@@ -243,12 +326,42 @@ moe_status moe_workspace_size(const moe_config* cfg, int32_t T_max, size_t* byte
     st = check_T(cfg, T_max);
     if (st != MOE_OK) return st;
     *bytes = carve_workspace(make_dims(*cfg, T_max)).total;
+    // a caller sizes its workspace before its first launch: take the chance to do the per-device set-up, so
+    // that even a first call made under stream capture finds it done (no device, e.g. a CPU-only host: skip)
+    if (ensure_device_init(nullptr) != hipSuccess) (void)hipGetLastError();
     return MOE_OK;
 }
 
-moe_status moe_route(const moe_config* cfg, const void* x, int32_t T, const float* gate_w, const float* gate_bias,
-                     double threshold, int32_t use_full_brownout, const moe_route_out* out, void* workspace,
-                     size_t workspace_bytes, void* stream)
+moe_status moe_init(void)
+{
+    hipError_t e = ensure_device_init(nullptr);
+    return e == hipSuccess ? MOE_OK : hip_fail(e, "moe_init");
+}
+
+moe_status moe_gate_packed_size(const moe_config* cfg, size_t* bytes)
+{
+    moe_status st = check_config(cfg);
+    if (st != MOE_OK) return st;
+    if (!bytes) return MOE_ERR_INVALID_ARG;
+    *bytes = (size_t)3 * (ceil_div(cfg->n_experts, 16) * 16) * cfg->d_model * 2;
+    return MOE_OK;
+}
+
+moe_status moe_pack_gate(const moe_config* cfg, const float* gate_w, void* packed, size_t packed_bytes, void* stream)
+{
+    moe_status st = check_config(cfg);
+    if (st != MOE_OK) return st;
+    if (!gate_w || !packed) return MOE_ERR_INVALID_ARG;
+    if (misaligned(gate_w) || misaligned(packed)) return MOE_ERR_ALIGNMENT;
+    const int m_pad = ceil_div(cfg->n_experts, 16) * 16;
+    if (packed_bytes < (size_t)3 * m_pad * cfg->d_model * 2) return MOE_ERR_WORKSPACE;
+    hipError_t e = launch_pack_gate(gate_w, cfg->n_experts, m_pad, cfg->d_model, static_cast<bf16_t*>(packed),
+                                    static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? MOE_OK : hip_fail(e, "moe_pack_gate");
+}
+
+static moe_status check_route_args(const moe_config* cfg, const void* x, int32_t T, const void* gate_w,
+                                   const float* gate_bias, double threshold, const moe_route_out* out)
 {
     moe_status st = check_config(cfg);
     if (st != MOE_OK) return st;
@@ -258,7 +371,14 @@ moe_status moe_route(const moe_config* cfg, const void* x, int32_t T, const floa
     if (!(threshold >= 0.0 && threshold <= 1.0)) return MOE_ERR_INVALID_ARG;
     if (misaligned(x) || misaligned(gate_w) || (gate_bias && (reinterpret_cast<uintptr_t>(gate_bias) & 3u)))
         return MOE_ERR_ALIGNMENT;
-    st = check_route_ptr_alignment(out);
+    return check_route_ptr_alignment(out);
+}
+
+moe_status moe_route(const moe_config* cfg, const void* x, int32_t T, const void* gate_w, const float* gate_bias,
+                     double threshold, int32_t use_full_brownout, const moe_route_out* out, void* workspace,
+                     size_t workspace_bytes, void* stream)
+{
+    moe_status st = check_route_args(cfg, x, T, gate_w, gate_bias, threshold, out);
     if (st != MOE_OK) return st;
     const Dims D = make_dims(*cfg, T);
     const Workspace W = carve_workspace(D);
@@ -266,14 +386,17 @@ moe_status moe_route(const moe_config* cfg, const void* x, int32_t T, const floa
     if (reinterpret_cast<uintptr_t>(workspace) & 255u) return MOE_ERR_ALIGNMENT;
     const RouteBufs R = resolve_route(out, workspace, W);
     hipStream_t s = static_cast<hipStream_t>(stream);
+    TileJobs none;
+    none.n = 0; none.cap = 0;
     hipError_t e = launch_route(D, static_cast<const bf16_t*>(x), gate_w, gate_bias, threshold,
                                 use_full_brownout ? 1 : 0, R, at<bf16_t>(workspace, W.gate_split),
-                                at<int32_t>(workspace, W.seg_cnt), at<int32_t>(workspace, W.seg_off), s);
+                                at<int32_t>(workspace, W.seg_cnt), at<int32_t>(workspace, W.seg_off),
+                                at<int32_t>(workspace, W.gate_hist), none, s);
     if (e != hipSuccess) return hip_fail(e, "moe_route");
     return MOE_OK;
 }
 
-moe_status moe_forward(const moe_config* cfg, const void* x, int32_t T, const float* gate_w, const float* gate_bias,
+moe_status moe_forward(const moe_config* cfg, const void* x, int32_t T, const void* gate_w, const float* gate_bias,
                        const moe_ffn_weights* experts, const moe_ffn_weights* united, const moe_ffn_weights* shared,
                        double threshold, int32_t use_full_brownout, const moe_route_out* route, void* out,
                        void* workspace, size_t workspace_bytes, void* stream)
@@ -316,36 +439,42 @@ moe_status moe_forward(const moe_config* cfg, const void* x, int32_t T, const fl
     const RouteBufs R = resolve_route(route, workspace, W);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bf16_t* xb = static_cast<const bf16_t*>(x);
+    // How the rows are cut into GEMM tiles: routed + united units by the expected rows per expert; shared units
+    // (T rows each) with them when they have the same width, else in a launch of their own.
+    const bool split_shared = D.Ns > 0 && D.Fs != D.F;
+    TileJobs jobs;
+    jobs.n = split_shared ? 2 : 1;
+    jobs.cap = D.tile_cap;
+    jobs.job[0].u_lo = 0; jobs.job[0].u_hi = split_shared ? D.m + D.G : D.U;
+    jobs.job[0].plan = make_tile_plan((int64_t)T * D.K / D.m);
+    jobs.job[0].table = at<int32_t>(workspace, W.tiles0);
+    jobs.job[1].u_lo = D.m + D.G; jobs.job[1].u_hi = D.U;
+    jobs.job[1].plan = make_tile_plan(T);
+    jobs.job[1].table = at<int32_t>(workspace, W.tiles1);
     hipError_t e;
     if (!route) {
         e = launch_route(D, xb, gate_w, gate_bias, threshold, use_full_brownout ? 1 : 0, R,
                          at<bf16_t>(workspace, W.gate_split), at<int32_t>(workspace, W.seg_cnt),
-                         at<int32_t>(workspace, W.seg_off), s);
+                         at<int32_t>(workspace, W.seg_off), at<int32_t>(workspace, W.gate_hist), jobs, s);
         if (e != hipSuccess) return hip_fail(e, "moe_forward/route");
     }
+    const bool built = route == nullptr;
     const FfnWeights fe = to_ffn(experts), fu = to_ffn(united), fs = to_ffn(shared);
     bf16_t* H = at<bf16_t>(workspace, W.H);
     bf16_t* Y = at<bf16_t>(workspace, W.Y);
     float* partial = W.partial_bytes ? at<float>(workspace, W.partial) : nullptr;
-    const int64_t rows_per_expert = (int64_t)T * D.K / D.m;
-    if (D.Ns > 0 && D.Fs != D.F) {
-        e = launch_ffn(D, 0, D.m + D.G, D.F, rows_per_expert, xb, R.row_token, R.unit_cnt, R.unit_off,
-                       fe, fu, fs, at<int32_t>(workspace, W.tiles0), H, Y, partial, s);
-        if (e != hipSuccess) return hip_fail(e, "moe_forward/ffn");
-        e = launch_ffn(D, D.m + D.G, D.U, D.Fs, T, xb, R.row_token, R.unit_cnt, R.unit_off, fe, fu, fs,
-                       at<int32_t>(workspace, W.tiles1), H, Y, partial, s);
-        if (e != hipSuccess) return hip_fail(e, "moe_forward/ffn_shared");
-    } else {
-        e = launch_ffn(D, 0, D.U, D.F, rows_per_expert, xb, R.row_token, R.unit_cnt, R.unit_off, fe, fu,
-                       fs, at<int32_t>(workspace, W.tiles0), H, Y, partial, s);
-        if (e != hipSuccess) return hip_fail(e, "moe_forward/ffn");
+    for (int j = 0; j < jobs.n; ++j) {
+        const TileJob& J = jobs.job[j];
+        e = launch_ffn(D, J.u_lo, J.u_hi, j == 0 ? D.F : D.Fs, J.plan, xb, R.row_token, R.unit_cnt, R.unit_off, fe, fu,
+                       fs, J.table, built, H, Y, partial, s);
+        if (e != hipSuccess) return hip_fail(e, j == 0 ? "moe_forward/ffn" : "moe_forward/ffn_shared");
     }
     e = launch_combine(D, xb, Y, R.token_rows, R.row_weight, static_cast<bf16_t*>(out), s);
     if (e != hipSuccess) return hip_fail(e, "moe_forward/combine");
     return MOE_OK;
 }
 
-moe_status moe_build_united(const moe_config* cfg, const moe_ffn_weights* experts, const moe_ffn_weights* united_out,
+moe_status moe_build_united(const moe_config* cfg, const moe_ffn_weights* experts, const moe_ffn_weights_out* united_out,
                             const void* calib_x, int32_t n_calib, float* loss_per_group, void* workspace,
                             size_t workspace_bytes, void* stream)
 {
@@ -353,7 +482,9 @@ moe_status moe_build_united(const moe_config* cfg, const moe_ffn_weights* expert
     if (st != MOE_OK) return st;
     st = check_weights(experts);
     if (st != MOE_OK) return st;
-    st = check_weights(united_out);
+    if (!united_out) return MOE_ERR_INVALID_ARG;
+    const moe_ffn_weights united_ro{united_out->w1, united_out->w3, united_out->w2};
+    st = check_weights(&united_ro);
     if (st != MOE_OK) return st;
     if (n_calib < 0) return MOE_ERR_INVALID_ARG;
     const bool want_loss = calib_x != nullptr && loss_per_group != nullptr && n_calib > 0;
@@ -367,22 +498,22 @@ moe_status moe_build_united(const moe_config* cfg, const moe_ffn_weights* expert
         st = check_T(cfg, n_calib);
         if (st != MOE_OK) return st;
         D = make_dims(*cfg, n_calib);
-        D.ksplit = 1;          // the loss kernel reads single-plane FFN outputs
         W = carve_workspace(D);
+        D.ksplit = 1;          // the loss kernel reads single-plane FFN outputs (the carving does not depend on it)
         if (!workspace || workspace_bytes < W.total) return MOE_ERR_WORKSPACE;
         if (reinterpret_cast<uintptr_t>(workspace) & 255u) return MOE_ERR_ALIGNMENT;
     }
     hipError_t e;
     const void* src[3] = {experts->w1, experts->w3, experts->w2};
-    void* dst[3] = {const_cast<void*>(united_out->w1), const_cast<void*>(united_out->w3),
-                    const_cast<void*>(united_out->w2)};
+    void* dst[3] = {united_out->w1, united_out->w3, united_out->w2};
     for (int k = 0; k < 3; ++k) {
         e = launch_united_mean(static_cast<const bf16_t*>(src[k]), m, way, n_elem, static_cast<bf16_t*>(dst[k]), s);
         if (e != hipSuccess) return hip_fail(e, "moe_build_united/mean");
     }
     if (!want_loss) return MOE_OK;
 
-    const FfnWeights fe = to_ffn(experts), fu = to_ffn(united_out), fs{nullptr, nullptr, nullptr};
+    const FfnWeights fe = to_ffn(experts), fu = to_ffn(&united_ro), fs{nullptr, nullptr, nullptr};
+    const TilePlan plan = make_tile_plan(n_calib);
     int32_t* unit_cnt = at<int32_t>(workspace, W.unit_cnt);
     int32_t* unit_off = at<int32_t>(workspace, W.unit_off);
     float* ones = at<float>(workspace, W.ones);
@@ -396,7 +527,7 @@ moe_status moe_build_united(const moe_config* cfg, const moe_ffn_weights* expert
     auto run_unit = [&](int u, bf16_t* Y) -> hipError_t {
         hipError_t err = launch_single_unit(unit_cnt, unit_off, D.U, u, n_calib, ones, s);
         if (err != hipSuccess) return err;
-        return launch_ffn(D, u, u + 1, D.F, n_calib, xb, nullptr, unit_cnt, unit_off, fe, fu, fs, tiles, H, Y,
+        return launch_ffn(D, u, u + 1, D.F, plan, xb, nullptr, unit_cnt, unit_off, fe, fu, fs, tiles, false, H, Y,
                           W.partial_bytes ? at<float>(workspace, W.partial) : nullptr, s);
     };
     for (int g = 0; g < G; ++g) {
@@ -427,13 +558,12 @@ moe_status moe_distill_workspace_size(const moe_config* cfg, int32_t n_calib, si
     if (!bytes) return MOE_ERR_INVALID_ARG;
     moe_status st = check_distill(cfg, n_calib);
     if (st != MOE_OK) return st;
-    Dims D = make_dims(*cfg, n_calib);
-    D.ksplit = 1;
+    const Dims D = make_dims(*cfg, n_calib);
     *bytes = align_up(carve_workspace(D).total, 256) + distill_buffer_bytes(n_calib, D.d, D.F);
     return MOE_OK;
 }
 
-moe_status moe_distill_united(const moe_config* cfg, const moe_ffn_weights* experts, const moe_ffn_weights* united,
+moe_status moe_distill_united(const moe_config* cfg, const moe_ffn_weights* experts, const moe_ffn_weights_out* united,
                               const void* calib_x, int32_t n_calib, int32_t steps, float lr, float* loss_history,
                               void* workspace, size_t workspace_bytes, void* stream)
 {
@@ -441,20 +571,23 @@ moe_status moe_distill_united(const moe_config* cfg, const moe_ffn_weights* expe
     if (st != MOE_OK) return st;
     st = check_weights(experts);
     if (st != MOE_OK) return st;
-    st = check_weights(united);
+    if (!united) return MOE_ERR_INVALID_ARG;
+    const moe_ffn_weights united_ro{united->w1, united->w3, united->w2};
+    st = check_weights(&united_ro);
     if (st != MOE_OK) return st;
     if (!calib_x || steps < 0 || !(lr >= 0.0f)) return MOE_ERR_INVALID_ARG;
     if (misaligned(calib_x)) return MOE_ERR_ALIGNMENT;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int m = cfg->n_experts, way = cfg->way, G = ceil_div(m, way);
     Dims D = make_dims(*cfg, n_calib);
-    D.ksplit = 1;
     const Workspace W = carve_workspace(D);
+    D.ksplit = 1;
+    const TilePlan plan = make_tile_plan(n_calib);
     const size_t fwd_bytes = align_up(W.total, 256);
     if (!workspace || workspace_bytes < fwd_bytes + distill_buffer_bytes(n_calib, D.d, D.F)) return MOE_ERR_WORKSPACE;
     if (reinterpret_cast<uintptr_t>(workspace) & 255u) return MOE_ERR_ALIGNMENT;
     void* buf = static_cast<char*>(workspace) + fwd_bytes;
-    const FfnWeights fe = to_ffn(experts), fu = to_ffn(united), fs{nullptr, nullptr, nullptr};
+    const FfnWeights fe = to_ffn(experts), fu = to_ffn(&united_ro), fs{nullptr, nullptr, nullptr};
     int32_t* unit_cnt = at<int32_t>(workspace, W.unit_cnt);
     int32_t* unit_off = at<int32_t>(workspace, W.unit_off);
     float* ones = at<float>(workspace, W.ones);
@@ -469,14 +602,13 @@ moe_status moe_distill_united(const moe_config* cfg, const moe_ffn_weights* expe
     auto teacher = [&](int i) -> hipError_t {
         hipError_t err = launch_single_unit(unit_cnt, unit_off, D.U, i, n_calib, ones, s);
         if (err != hipSuccess) return err;
-        return launch_ffn(D, i, i + 1, D.F, n_calib, xb, nullptr, unit_cnt, unit_off, fe, fu, fs, tiles, H, Yo,
+        return launch_ffn(D, i, i + 1, D.F, plan, xb, nullptr, unit_cnt, unit_off, fe, fu, fs, tiles, false, H, Yo,
                           W.partial_bytes ? at<float>(workspace, W.partial) : nullptr, s);
     };
     for (int g = 0; g < G; ++g) {
         const int lo = g * way, hi = lo + way < m ? lo + way : m, k = hi - lo;
-        bf16_t* wu[3] = {static_cast<bf16_t*>(const_cast<void*>(united->w1)) + (size_t)g * dF,
-                         static_cast<bf16_t*>(const_cast<void*>(united->w3)) + (size_t)g * dF,
-                         static_cast<bf16_t*>(const_cast<void*>(united->w2)) + (size_t)g * dF};
+        bf16_t* wu[3] = {static_cast<bf16_t*>(united->w1) + (size_t)g * dF, static_cast<bf16_t*>(united->w3) + (size_t)g * dF,
+                         static_cast<bf16_t*>(united->w2) + (size_t)g * dF};
         if (k == 1) {
             // a lone member is its own best student: the minimiser (loss 0) is known, nothing to train
             const void* we[3] = {experts->w1, experts->w3, experts->w2};

@@ -14,15 +14,17 @@
 // so skewed expert loads need no host round trip.  Each XCD (block id mod 8) works on a contiguous range
 // of tiles, ordered so that the blocks it runs at a time share A and B panels in its own L2.
 //
-// Kernels, by tile height (chosen on the host from the expected rows per unit):
+// Kernels, by tile height (chosen on the host from the expected rows per unit; all tiles of a unit, its ragged
+// last one included, stay next to each other in the tile order, because they share the unit's weight panels
+// in the L2 of the XCD that runs them):
 //   256 rows  ffn_gemm_w4_kernel   four waves, one per SIMD, 128x128 wave tiles, 16x16x32 MFMA, persistent;
 //                                  further blocks of the same launch take the tiles left over after the last
 //                                  full round: cut along K (fp32 partial tiles, summed by
 //                                  gemm_tail_sum_kernel) or in two along N
-//             ffn_gemm_rs_kernel   eight waves, register-staged; stand-in when A offsets exceed 32 bits
 //   128 rows  ffn_gemm_pp_kernel   eight waves in two groups that alternate memory and MFMA phases
 //   64, 32    ffn_gemm_kernel      four waves, plain multi-stage ring (decode: weight streaming bound)
 #include "internal.h"
+#include "tiles.h"
 
 #include <algorithm>
 #include <cstdlib>
@@ -58,46 +60,14 @@ __device__ __forceinline__ float swiglu(float g, float u)
 }
 
 // ------------------------------------------------------------------------------------------------
-// Tile table: header {n_mtiles, 0, 0, 0} then one int4 {unit, first row, rows, 0} per M tile, units in
-// ascending order, tiles of a unit consecutive.  One block.
+// Tile tables from the unit counts, when the routing kernels have not already built them (row lists brought
+// by the caller; single units of the united-expert build): one wavefront per job.
 // ------------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) tile_table_kernel(const int32_t* __restrict__ unit_cnt,
-                                                         const int32_t* __restrict__ unit_off, int u_lo, int u_hi,
-                                                         int BM, int32_t* __restrict__ table, int cap)
+__global__ void __launch_bounds__(64) tile_table_kernel(const int32_t* __restrict__ unit_cnt,
+                                                        const int32_t* __restrict__ unit_off, TileJobs jobs)
 {
-    __shared__ int wsum[4];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int n_units = u_hi - u_lo;
-    const int per = (n_units + 255) / 256;
-    int local = 0;
-    for (int q = 0; q < per; ++q) {
-        const int u = u_lo + tid * per + q;
-        if (u < u_hi) local += (unit_cnt[u] + BM - 1) / BM;
-    }
-    int incl = local;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const int o = __shfl_up(incl, off);
-        if (lane >= off) incl += o;
-    }
-    if (lane == 63) wsum[wave] = incl;
-    __syncthreads();
-    int base = incl - local;
-    for (int w = 0; w < wave; ++w) base += wsum[w];
-    int4* entries = reinterpret_cast<int4*>(table + 4);
-    for (int q = 0; q < per; ++q) {
-        const int u = u_lo + tid * per + q;
-        if (u >= u_hi) break;
-        const int c = unit_cnt[u], o = unit_off[u];
-        for (int r = 0; r < c; r += BM) {
-            if (base < cap) entries[base] = make_int4(u, o + r, min(BM, c - r), 0);
-            ++base;
-        }
-    }
-    if (tid == 255) {
-        table[0] = min(base, cap);
-        table[1] = 0; table[2] = 0; table[3] = 0;
-    }
+    if ((int)blockIdx.x < jobs.n)
+        build_tile_table(unit_cnt, unit_off, jobs.job[blockIdx.x], jobs.cap, threadIdx.x);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -112,7 +82,6 @@ struct GemmArgs {
     int n_ntiles;
     int group_m;                                // M tiles per L2 super-tile
     int ksplit; long plane;                     // GEMM2 only: K split into ksplit slices, slice s writes out + s*plane
-    int a_fits_32;                              // every byte offset into A fits 32 bits (gathered A rows)
     float* out32;                               // plain GEMM only (32- and 64-row kernel): fp32 output instead of out
     float* partial;                             // four-wave kernel, ksplit 1: scratch of the K-split tail (or null)
     int partial_cap;                            // fp32 tiles it holds
@@ -546,21 +515,6 @@ __global__ void __launch_bounds__(512) ffn_gemm_pp_kernel(GemmArgs p)
     store_tile<FM, FN, TM, TN, SWIGLU>(p, t, acc, wm, wn, lane);
 }
 
-// ------------------------------------------------------------------------------------------------
-// Register-staged large-tile kernel (BM x 256 x 64, 8 waves as 2 x 4, same ping-pong as above) with a
-// three-deep pipeline out of two LDS buffers: while tile kt is multiplied out of one buffer, tile kt+1
-// sits in registers (it was requested during tile kt-1) and is written to the other buffer in this tile's
-// memory phases, and tile kt+2 is requested between the MFMAs of the compute phases.  A load has a full
-// tile time to return, and only plain vector loads and LDS stores are used in the loop.  Past the end
-// of K the loads are clamped to the last tile (their data is never read).
-// ------------------------------------------------------------------------------------------------
-// The compiler's own wait insertion would drain every load before the first LDS store of a tile, so the
-// staging loads are opaque to it and waited for by hand (s_waitcnt vmcnt) before their registers are read.
-__device__ __forceinline__ void load_stage(u32x4& dst, const bf16_t* src)
-{
-    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(dst) : "v"(src));
-}
-
 // Tells the compiler that a pointer is the same in every lane (keeps it in scalar registers).
 __device__ __forceinline__ const bf16_t* uniform_ptr(const bf16_t* ptr)
 {
@@ -568,122 +522,6 @@ __device__ __forceinline__ const bf16_t* uniform_ptr(const bf16_t* ptr)
     const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
     const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
     return reinterpret_cast<const bf16_t*>(((unsigned long long)hi << 32) | lo);
-}
-
-template <int BM, bool SWIGLU>
-__global__ void __launch_bounds__(512) ffn_gemm_rs_kernel(GemmArgs p)
-{
-    constexpr int BK = 64, BN = 256, WN = 4, NW = 8, P = 2;
-    using L = Lds<BK>;
-    constexpr int TM = BM / 2, TN = BN / WN, FM = TM / 16, FN = TN / 16;
-    constexpr int RB = L::RB, RPG = L::RPG;
-    constexpr int STAGE = (BM + BN) * RB;
-    constexpr int GROUPS = (BM + BN) / RPG;
-    constexpr int LD_PER_WAVE = GROUPS / NW;
-    constexpr int LP = LD_PER_WAVE / P;                  // loads (and LDS stores) per phase
-    constexpr int NM = FM * FN;                          // MFMAs (16x16x32) per compute phase
-    constexpr int EV = NM / LP;
-    static_assert(GROUPS % NW == 0 && LD_PER_WAVE % P == 0 && EV >= 1, "loader shape");
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-
-    Tile t;
-    if (!decode_tile<SWIGLU ? BN / 2 : BN, SWIGLU>(p, t)) return;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 2, wn = wave & 3;
-    const int grp = wm;
-    int k_first, nk;
-    k_range<BK>(p, t, k_first, nk);
-
-    const bf16_t* gptr[LD_PER_WAVE];
-#pragma unroll
-    for (int i = 0; i < LD_PER_WAVE; ++i) {
-        const int row = (wave + i * NW) * RPG + L::lane_row(lane);
-        const bf16_t* base = row < BM ? a_row_ptr(p, t, row) : b_row_ptr<TN, SWIGLU, 16>(p, t, row - BM);
-        gptr[i] = base + L::lane_chunk(lane, row) * 8 + (size_t)k_first * BK;
-    }
-    f32x4 acc[FM][FN];
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-            for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.0f;
-    if (nk <= 0) {
-        store_tile16<FM, FN, TM, TN, SWIGLU>(p, t, acc, wm, wn, lane);
-        return;
-    }
-    const int last = nk - 1;
-    // tile 0 straight into buffer 0, tile 1 into registers
-    {
-        char* dst = smem + wave * 1024;
-#pragma unroll
-        for (int i = 0; i < LD_PER_WAVE; ++i)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gptr[i],
-                                             (__attribute__((address_space(3))) void*)(dst + i * NW * 1024), 16, 0, 0);
-    }
-    u32x4 stg[LD_PER_WAVE];
-#pragma unroll
-    for (int i = 0; i < LD_PER_WAVE; ++i) load_stage(stg[i], gptr[i] + min(1, last) * BK);
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(LD_PER_WAVE));   // the LDS loads are the older ones
-    const int a_off = (wm * TM + (lane & 15)) * RB;
-    const int b_off = BM * RB + (wn * TN + (lane & 15)) * RB;
-    const int w_off = wave * 1024 + lane * 16;
-    const int swz = ((lane & 15) / L::WR) & (L::CPR - 1);
-    lds_barrier();                                        // tile 0 is in LDS for everyone
-    if (grp == 1) lds_barrier();
-    for (int kt = 0; kt < nk; ++kt) {
-        const char* St = smem + (kt & 1) * STAGE;
-        char* Wn = smem + ((kt + 1) & 1) * STAGE + w_off;  // buffer of tile kt-1: both groups have left it
-        const long knext = (long)min(kt + 2, last) * BK;
-#pragma unroll
-        for (int ph = 0; ph < P; ++ph) {
-            // -- memory phase: this step's fragments out of LDS, then this phase's share of tile kt+1 into LDS
-            bf16x8 af[FM], bfr[FN];
-            {
-                const int sw = ((ph * 4 + (lane >> 4)) ^ swz) << 4;
-#pragma unroll
-                for (int i = 0; i < FM; ++i) af[i] = *reinterpret_cast<const bf16x8*>(St + a_off + i * 16 * RB + sw);
-#pragma unroll
-                for (int j = 0; j < FN; ++j) bfr[j] = *reinterpret_cast<const bf16x8*>(St + b_off + j * 16 * RB + sw);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            // in flight: this phase's LP registers (requested a tile ago) and the LP requested one compute
-            // phase ago; loads return in order
-            __builtin_amdgcn_s_waitcnt(vmcnt_imm(LP));
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int q = 0; q < LP; ++q)
-                *reinterpret_cast<u32x4*>(Wn + (ph * LP + q) * NW * 1024) = stg[ph * LP + q];
-            __builtin_amdgcn_s_waitcnt(0xC07F);           // lgkmcnt(0): fragments here, stores done
-            __builtin_amdgcn_sched_barrier(0);
-            lds_barrier();
-            __builtin_amdgcn_sched_barrier(0);
-            // -- compute phase, with this phase's share of tile kt+2 requested between the MFMAs
-            __builtin_amdgcn_s_setprio(1);
-#pragma unroll
-            for (int i = 0; i < FM; ++i)
-#pragma unroll
-                for (int j = 0; j < FN; ++j) {
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
-                    const int mi = i * FN + j;
-                    if (mi % EV == 0 && mi / EV < LP) {
-                        __builtin_amdgcn_sched_barrier(0);
-                        const int li = ph * LP + mi / EV;
-                        load_stage(stg[li], gptr[li] + knext);
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                }
-            __builtin_amdgcn_s_setprio(0);
-            __builtin_amdgcn_sched_barrier(0);
-            lds_barrier();
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
-    if (grp == 0) lds_barrier();
-    __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));             // the clamped tail loads still target stg
-#pragma unroll
-    for (int i = 0; i < LD_PER_WAVE; ++i) asm volatile("" ::"v"(stg[i]));
-    store_tile16<FM, FN, TM, TN, SWIGLU>(p, t, acc, wm, wn, lane);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -956,7 +794,10 @@ __device__ __forceinline__ void w4_block(const GemmArgs& p, const int block, con
     auto setup_tile = [&](const Tile& tt, int grows) {
         int k_first;
         k_range<BK>(p, tt, k_first, nk);
-        last = nk - 1;
+        // an empty K slice (more planes than k tiles): the first loads are still issued, from k tile 0, and
+        // never read; the tile is stored as zeros
+        if (nk <= 0) k_first = 0;
+        last = nk > 0 ? nk - 1 : 0;
         if (GATHER) {
 #pragma unroll
             for (int i = 0; i < HL; ++i)
@@ -1226,16 +1067,37 @@ __global__ void __launch_bounds__(256) combine_kernel(const bf16_t* __restrict__
 }
 
 // ------------------------------------------------------------------------------------------------
+// Launchers.  Kernels that need more dynamic LDS than the default limit get the attribute once per device in
+// init_ffn_kernels (never inside a launch path: the call is not allowed under stream capture).
+// ------------------------------------------------------------------------------------------------
+template <int BM, int BN, int WM, int WN, int BK, int NSTAGE>
+constexpr int small_lds() { return NSTAGE * (BM + BN) * BK * 2; }
+constexpr int kPpLds = 3 * (128 + 256) * 64 * 2;
+constexpr int kW4Lds = 160 * 1024;
+
 template <typename Kern>
-static hipError_t launch_tiles(Kern kern, bool& attr_set, int threads, int lds, int bn_cols, GemmArgs a, int max_mtiles,
-                               hipStream_t s)
+static hipError_t set_lds(Kern kern, int lds)
 {
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+}
+
+hipError_t init_ffn_kernels()
+{
+    hipError_t e;
+    if ((e = set_lds(ffn_gemm_kernel<64, 256, 1, 4, 64, 3, true>, small_lds<64, 256, 1, 4, 64, 3>())) != hipSuccess) return e;
+    if ((e = set_lds(ffn_gemm_kernel<64, 256, 1, 4, 64, 3, false>, small_lds<64, 256, 1, 4, 64, 3>())) != hipSuccess) return e;
+    if ((e = set_lds(ffn_gemm_kernel<32, 256, 1, 4, 64, 4, true>, small_lds<32, 256, 1, 4, 64, 4>())) != hipSuccess) return e;
+    if ((e = set_lds(ffn_gemm_kernel<32, 256, 1, 4, 64, 4, false>, small_lds<32, 256, 1, 4, 64, 4>())) != hipSuccess) return e;
+    if ((e = set_lds(ffn_gemm_pp_kernel<128, 64, 3, true>, kPpLds)) != hipSuccess) return e;
+    if ((e = set_lds(ffn_gemm_pp_kernel<128, 64, 3, false>, kPpLds)) != hipSuccess) return e;
+    if ((e = set_lds(ffn_gemm_w4_kernel<true>, kW4Lds)) != hipSuccess) return e;
+    if ((e = set_lds(ffn_gemm_w4_kernel<false>, kW4Lds)) != hipSuccess) return e;
+    return hipSuccess;
+}
+
+template <typename Kern>
+static hipError_t launch_tiles(Kern kern, int threads, int lds, int bn_cols, GemmArgs a, int max_mtiles, hipStream_t s)
+{
     a.n_ntiles = ceil_div(a.N, bn_cols);
     const long total = (long)max_mtiles * a.n_ntiles * a.ksplit;
     const int grid = (int)((total + 7) / 8 * 8);
@@ -1246,48 +1108,22 @@ static hipError_t launch_tiles(Kern kern, bool& attr_set, int threads, int lds, 
 template <int BM, int BN, int WM, int WN, int BK, int NSTAGE, bool SWIGLU>
 static hipError_t launch_small(const GemmArgs& a, int max_mtiles, hipStream_t s)
 {
-    constexpr int LDS = NSTAGE * (BM + BN) * BK * 2;
+    constexpr int LDS = small_lds<BM, BN, WM, WN, BK, NSTAGE>();
     static_assert(LDS <= 160 * 1024, "LDS budget of one CU");
-    static bool attr_set = false;
-    return launch_tiles(ffn_gemm_kernel<BM, BN, WM, WN, BK, NSTAGE, SWIGLU>, attr_set, WM * WN * 64, LDS,
-                        SWIGLU ? BN / 2 : BN, a, max_mtiles, s);
-}
-
-template <int BM, int BK, int NSTAGE, bool SWIGLU>
-static hipError_t launch_pp(const GemmArgs& a, int max_mtiles, hipStream_t s)
-{
-    constexpr int LDS = NSTAGE * (BM + 256) * BK * 2;
-    static bool attr_set = false;
-    return launch_tiles(ffn_gemm_pp_kernel<BM, BK, NSTAGE, SWIGLU>, attr_set, 512, LDS, SWIGLU ? 128 : 256, a, max_mtiles,
-                        s);
-}
-
-template <int BM, bool SWIGLU>
-static hipError_t launch_rs(const GemmArgs& a, int max_mtiles, hipStream_t s)
-{
-    constexpr int LDS = 2 * (BM + 256) * 64 * 2;
-    static bool attr_set = false;
-    return launch_tiles(ffn_gemm_rs_kernel<BM, SWIGLU>, attr_set, 512, LDS, SWIGLU ? 128 : 256, a, max_mtiles, s);
+    return launch_tiles(ffn_gemm_kernel<BM, BN, WM, WN, BK, NSTAGE, SWIGLU>, WM * WN * 64, LDS, SWIGLU ? BN / 2 : BN, a,
+                        max_mtiles, s);
 }
 
 template <bool SWIGLU>
-static hipError_t launch_w4(const GemmArgs& a, int max_mtiles, hipStream_t s)
+static hipError_t launch_pp(const GemmArgs& a, int max_mtiles, hipStream_t s)
 {
-    constexpr int LDS = 160 * 1024;
-    static bool attr_set = false;
-    static int n_cu = 0;
+    return launch_tiles(ffn_gemm_pp_kernel<128, 64, 3, SWIGLU>, 512, kPpLds, SWIGLU ? 128 : 256, a, max_mtiles, s);
+}
+
+template <bool SWIGLU>
+static hipError_t launch_w4(const GemmArgs& a, int max_mtiles, int n_cu, hipStream_t s)
+{
     auto kern = ffn_gemm_w4_kernel<SWIGLU>;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
-        if (e != hipSuccess) return e;
-        int dev = 0;
-        e = hipGetDevice(&dev);
-        if (e != hipSuccess) return e;
-        e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
     GemmArgs g = a;
     g.n_ntiles = ceil_div(g.N, SWIGLU ? 128 : 256);
     const long total = (long)max_mtiles * g.n_ntiles * g.ksplit;
@@ -1298,68 +1134,70 @@ static hipError_t launch_w4(const GemmArgs& a, int max_mtiles, hipStream_t s)
     // at most grid - 1 tiles are left over after the last full round of `grid` tiles
     const int max_tail = (int)std::min<long>(total, grid - 1);
     if (max_tail <= 0) g.partial = nullptr;
-    kern<<<g.partial ? 3 * grid : grid, 256, LDS, s>>>(g);
+    kern<<<g.partial ? 3 * grid : grid, 256, kW4Lds, s>>>(g);
     if (g.partial) gemm_tail_sum_kernel<SWIGLU><<<std::min(max_tail * 64, 2048), 256, 0, s>>>(g, grid);
     return hipGetLastError();
 }
 
 template <bool SWIGLU>
-static hipError_t dispatch_gemm(int BM, const GemmArgs& a, int max_mtiles, hipStream_t s)
+static hipError_t dispatch_gemm(int bm, const GemmArgs& a, int max_mtiles, int n_cu, hipStream_t s)
 {
-    switch (BM) {
-        case 256:
-            if (!a.a_fits_32 || std::getenv("BROWNOUT_MOE_RS")) return launch_rs<256, SWIGLU>(a, max_mtiles, s);
-            return launch_w4<SWIGLU>(a, max_mtiles, s);
-        case 128: return launch_pp<128, 64, 3, SWIGLU>(a, max_mtiles, s);
+    switch (bm) {
+        case 256: return launch_w4<SWIGLU>(a, max_mtiles, n_cu, s);
+        case 128: return launch_pp<SWIGLU>(a, max_mtiles, s);
         case 64: return launch_small<64, 256, 1, 4, 64, 3, SWIGLU>(a, max_mtiles, s);
         default: return launch_small<32, 256, 1, 4, 64, 4, SWIGLU>(a, max_mtiles, s);
     }
 }
 
-hipError_t launch_ffn(const Dims& D, int u_lo, int u_hi, int Fdim, int64_t expected_rows, const bf16_t* x,
+hipError_t launch_ffn(const Dims& D, int u_lo, int u_hi, int Fdim, const TilePlan& plan, const bf16_t* x,
                       const int32_t* gather, const int32_t* unit_cnt, const int32_t* unit_off,
-                      const FfnWeights& experts, const FfnWeights& united,
-                      const FfnWeights& shared, int32_t* tile_table, bf16_t* H, bf16_t* Y, float* partial, hipStream_t s)
+                      const FfnWeights& experts, const FfnWeights& united, const FfnWeights& shared,
+                      int32_t* table, bool table_built, bf16_t* H, bf16_t* Y, float* partial, hipStream_t s)
 {
+    DeviceInfo dev;
+    hipError_t e = ensure_device_init(&dev);
+    if (e != hipSuccess) return e;
     const int n_units = u_hi - u_lo;
-    const int BM = pick_tile_rows(expected_rows);
-    const int max_mtiles = (int)std::min<int64_t>(D.row_cap / BM + n_units, D.tile_cap);
-    {
+    if (!table_built) {
         ProfScope ps(MOE_STAGE_TILES, s);
-        tile_table_kernel<<<1, 256, 0, s>>>(unit_cnt, unit_off, u_lo, u_hi, BM, tile_table, D.tile_cap);
+        TileJobs jobs;
+        jobs.n = 1; jobs.cap = D.tile_cap;
+        jobs.job[0].u_lo = u_lo; jobs.job[0].u_hi = u_hi; jobs.job[0].plan = plan; jobs.job[0].table = table;
+        jobs.job[1] = jobs.job[0];
+        tile_table_kernel<<<1, 64, 0, s>>>(unit_cnt, unit_off, jobs);
     }
+    const int max_mtiles = (int)std::min<int64_t>(D.row_cap / plan.bm + n_units, D.tile_cap);
     GemmArgs g1;
-    g1.A = x; g1.lda = D.d; g1.gather = gather; g1.table = tile_table;
+    g1.A = x; g1.lda = D.d; g1.gather = gather; g1.table = nullptr;
     g1.wa0 = experts.w1; g1.wa1 = united.w1; g1.wa2 = shared.w1;
     g1.wb0 = experts.w3; g1.wb1 = united.w3; g1.wb2 = shared.w3;
     g1.m = D.m; g1.G = D.G; g1.N = Fdim; g1.K = D.d;
     g1.out = H; g1.ldo = D.Fmax;
-    g1.n_ntiles = 0;                            // set by launch_gemm from its tile width
-    int group_m = 4;
-    if (const char* e = std::getenv("BROWNOUT_MOE_GM")) group_m = std::max(1, std::atoi(e));
-    g1.group_m = group_m;
+    g1.n_ntiles = 0;                            // set by the launcher from its tile width
+    g1.group_m = tuning().group_m;
     g1.ksplit = 1; g1.plane = 0;
-    g1.a_fits_32 = (uint64_t)D.T * (uint64_t)D.d * 2 < (1ull << 32);
     g1.out32 = nullptr; g1.partial = partial; g1.partial_cap = D.tail_blocks;
+    g1.table = table;
     {
         ProfScope ps(MOE_STAGE_GEMM1, s);
-        hipError_t e = dispatch_gemm<true>(BM, g1, max_mtiles, s);
+        e = dispatch_gemm<true>(plan.bm, g1, max_mtiles, dev.n_cu, s);
         if (e != hipSuccess) return e;
     }
     GemmArgs g2;
-    g2.A = H; g2.lda = D.Fmax; g2.gather = nullptr; g2.table = tile_table;
+    g2.A = H; g2.lda = D.Fmax; g2.gather = nullptr; g2.table = nullptr;
     g2.wa0 = experts.w2; g2.wa1 = united.w2; g2.wa2 = shared.w2;
     g2.wb0 = g2.wb1 = g2.wb2 = nullptr;
     g2.m = D.m; g2.G = D.G; g2.N = D.d; g2.K = Fdim;
     g2.out = Y; g2.ldo = D.d;
     g2.n_ntiles = 0;
-    g2.group_m = group_m;
+    g2.group_m = tuning().group_m;
     g2.ksplit = D.ksplit; g2.plane = D.y_plane;
-    g2.a_fits_32 = 1;                           // rows of H are addressed relative to the tile
     g2.out32 = nullptr; g2.partial = partial; g2.partial_cap = D.tail_blocks;
+    g2.table = table;
     {
         ProfScope ps(MOE_STAGE_GEMM2, s);
-        hipError_t e = dispatch_gemm<false>(BM, g2, max_mtiles, s);
+        e = dispatch_gemm<false>(plan.bm, g2, max_mtiles, dev.n_cu, s);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
@@ -1386,8 +1224,8 @@ hipError_t launch_plain_gemm(const bf16_t* A, const bf16_t* B, int M, int N, int
     g.A = A; g.lda = K; g.gather = nullptr; g.table = table;
     g.wa0 = B; g.wa1 = g.wa2 = nullptr; g.wb0 = g.wb1 = g.wb2 = nullptr;
     g.m = 1; g.G = 0; g.N = N; g.K = K;
-    g.out = nullptr; g.ldo = N; g.n_ntiles = 0; g.group_m = 4; g.ksplit = 1; g.plane = 0; g.a_fits_32 = 1;
-    g.out32 = C; g.partial = nullptr; g.partial_cap = 0;
+    g.out = nullptr; g.ldo = N; g.n_ntiles = 0; g.group_m = 4; g.ksplit = 1; g.plane = 0;
+    g.out32 = C; g.partial = nullptr; g.partial_cap = 0; 
     return launch_small<64, 256, 1, 4, 64, 3, false>(g, n_mt, s);
 }
 

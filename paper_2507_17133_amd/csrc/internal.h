@@ -16,16 +16,41 @@ constexpr int kMaxTopK = 32;      // K
 constexpr int kMaxShared = 8;     // N_s
 constexpr int kMaxUnits = kMaxExperts + kMaxExperts + kMaxShared;  // U
 constexpr int kSegTokens = 64;    // tokens per routing segment (one wavefront)
+constexpr int kSmallSegs = 16;    // batches of at most this many segments are routed by ONE block
+constexpr int kSmallRouteTokens = kSmallSegs * kSegTokens;
 constexpr int kMinTileRows = 32;  // smallest GEMM M tile
 constexpr int kTailBlocks = 256;  // largest grid of the persistent GEMM whose K-split tail has scratch (one block per CU)
 
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// Measurement switches, read from the environment ONCE (when the library is loaded); all unset in normal use.
+struct Tuning {
+    int force_bm;      // BROWNOUT_MOE_BM = 32/64/128/256: one tile height for every unit (0: not forced)
+    int group_m;       // BROWNOUT_MOE_GM: M tiles per L2 super-tile of the GEMMs (default 4)
+    int force_ksplit;  // BROWNOUT_MOE_KSPLIT = 1/2/4: K planes of GEMM2 with small tiles (0: not forced)
+};
+const Tuning& tuning();
+
+// One-time set-up per device: kernel attributes (dynamic LDS sizes), CU count.  Done by moe_init and by
+// moe_workspace_size; the launch paths only check that it has happened (and do it if not, which works
+// everywhere except under stream capture).
+struct DeviceInfo { int n_cu; };
+hipError_t ensure_device_init(DeviceInfo* info);
+hipError_t init_ffn_kernels();      // ffn.hip
+hipError_t init_route_kernels();    // route.hip
+
+// How the rows of the units are cut into GEMM M tiles: one tile height for every unit of a launch, decided on
+// the host from the expected rows per unit (the real counts stay on the device).
+struct TilePlan {
+    int bm;      // 256, 128, 64 or 32
+};
+TilePlan make_tile_plan(int64_t expected_rows_per_unit);
+
 // Derived sizes of one (config, T) problem.
 struct Dims {
     int T, d, F, m, K, way, G, Ns, Fs, U, slots, m_pad, Fmax;
-    int score_fn, add_residual;
+    int score_fn, add_residual, gate_format;
     int64_t row_cap;   // rows the row lists can hold: T*(K+Ns)
     int n_seg;         // routing segments
     int tile_cap;      // entries of one GEMM tile table
@@ -34,8 +59,6 @@ struct Dims {
     int tail_blocks;   // fp32 tiles in the scratch of the persistent GEMM's K-split tail (a bound on its grid)
 };
 Dims make_dims(const moe_config& c, int T);
-// GEMM tile height from the expected rows per expert (the real counts stay on the device).
-int pick_tile_rows(int64_t expected_rows_per_unit);
 
 // Carving of the caller's workspace.  All offsets are multiples of 256 bytes.
 struct Workspace {
@@ -43,6 +66,8 @@ struct Workspace {
         token_rows, n_rows, near_tie;                 // default homes of the moe_route_out fields
     size_t gate_split;                                // [3][m_pad][d] bf16
     size_t seg_cnt, seg_off;                          // [n_seg][U] int32
+    size_t gate_hist;                                 // [blocks of the gate][m_pad] int32 (small batches only)
+    size_t route_total;                               // bytes of the pieces above (all that routing alone needs)
     size_t tiles0, tiles1;                            // two GEMM tile tables: int32[4] header + int4 entries
     size_t H;                                         // [h_rows][Fmax] bf16
     size_t Y;                                         // [y_rows][d], IEEE half (2 bytes; carried as bf16_t*)
@@ -70,19 +95,26 @@ struct ProfScope {
 };
 
 // ---- routing (route.hip) ----
-hipError_t launch_route(const Dims& D, const bf16_t* x, const float* gate_w, const float* gate_bias,
+struct TileJobs;
+// gate: fp32 [m][d] (D.gate_format MOE_GATE_FP32; split into gate_split on the way) or the packed pieces
+// (MOE_GATE_PACKED; gate_split unused).  jobs: GEMM tile tables to build once the unit counts are known
+// (jobs.n == 0: none).
+hipError_t launch_route(const Dims& D, const bf16_t* x, const void* gate, const float* gate_bias,
                         double threshold, int full_brownout, const RouteBufs& R, bf16_t* gate_split,
-                        int32_t* seg_cnt, int32_t* seg_off, hipStream_t s);
+                        int32_t* seg_cnt, int32_t* seg_off, int32_t* gate_hist, const TileJobs& jobs, hipStream_t s);
+hipError_t launch_pack_gate(const float* gate_w, int m, int m_pad, int d, bf16_t* packed, hipStream_t s);
 
 // ---- FFN (ffn.hip) ----
 struct FfnWeights { const bf16_t *w1, *w3, *w2; };
 // Runs W2(silu(W1 x)*(W3 x)) for the rows of units [u_lo,u_hi) listed in (unit_cnt, unit_off, gather),
 // writes Y[row][d] = FFN(x[gather ? gather[row] : row]) (the row weights are applied by the combine).  Fdim is the FFN width of
 // these units.  Weight source of unit u: u<m experts[u]; u<m+G united[u-m]; else shared[u-m-G].
-hipError_t launch_ffn(const Dims& D, int u_lo, int u_hi, int Fdim, int64_t expected_rows, const bf16_t* x,
+// plan / table: how the rows are cut into M tiles and where the tile table lives; table_built: the routing
+// kernels have already written it (else a small kernel does, from unit_cnt / unit_off).
+hipError_t launch_ffn(const Dims& D, int u_lo, int u_hi, int Fdim, const TilePlan& plan, const bf16_t* x,
                       const int32_t* gather, const int32_t* unit_cnt, const int32_t* unit_off,
-                      const FfnWeights& experts, const FfnWeights& united,
-                      const FfnWeights& shared, int32_t* tile_table, bf16_t* H, bf16_t* Y, float* partial, hipStream_t s);
+                      const FfnWeights& experts, const FfnWeights& united, const FfnWeights& shared,
+                      int32_t* table, bool table_built, bf16_t* H, bf16_t* Y, float* partial, hipStream_t s);
 hipError_t launch_combine(const Dims& D, const bf16_t* x, const bf16_t* Y, const int32_t* token_rows,
                           const float* row_weight, bf16_t* out, hipStream_t s);
 

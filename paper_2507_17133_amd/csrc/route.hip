@@ -8,6 +8,7 @@
 //   scatter  row lists: row_token, row_weight, token_rows (stable: ascending token inside a unit)
 // No floating-point atomics anywhere; integer atomics only where the result does not depend on order.
 #include "internal.h"
+#include "tiles.h"
 
 #include <algorithm>
 
@@ -32,9 +33,9 @@ __device__ __forceinline__ float bf16_bits_to_f32(unsigned short b) { return __u
 __global__ void __launch_bounds__(256) prep_kernel(const float* __restrict__ gate_w, int m, int m_pad, int d,
                                                    unsigned short* __restrict__ split, int32_t* __restrict__ expert_cnt)
 {
-    const size_t n = (size_t)m_pad * d;
+    const size_t n = split != nullptr ? (size_t)m_pad * d : 0;   // split == nullptr: only clear the counters
     const size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (gid < (size_t)m) expert_cnt[gid] = 0;
+    if (expert_cnt != nullptr && gid < (size_t)m) expert_cnt[gid] = 0;
     for (size_t i = gid; i < n; i += (size_t)gridDim.x * blockDim.x) {
         const int e = (int)(i / d);
         const float w = e < m ? gate_w[i] : 0.0f;
@@ -61,6 +62,7 @@ struct GateArgs {
     const bf16_t* x; const unsigned short* split; const float* bias;
     int T, d, m, m_pad, K, score_fn, NG, KS, n_stage;
     int32_t* topk_idx; float* topk_w; int32_t* expert_cnt; uint8_t* near_tie;
+    int32_t* block_hist;   // [blocks][m_pad]: per-block expert counts instead of atomics on expert_cnt (or null)
 };
 
 // TopK(.,K) of one token by one wavefront: lane holds experts lane, lane+64, ...; K (+1 for the best
@@ -313,8 +315,12 @@ __global__ void __launch_bounds__(1024) gate_topk_kernel(GateArgs p)
     // TopK: one token per wavefront
     if (t0 + wave < p.T) topk_token(p, logit + wave * p.m_pad, t0 + wave, lane, hist);
     __syncthreads();
-    for (int i = tid; i < p.m; i += 1024)
-        if (hist[i] > 0) atomicAdd(&p.expert_cnt[i], hist[i]);
+    if (p.block_hist != nullptr) {
+        for (int i = tid; i < p.m_pad; i += 1024) p.block_hist[(size_t)blockIdx.x * p.m_pad + i] = hist[i];
+    } else {
+        for (int i = tid; i < p.m; i += 1024)
+            if (hist[i] > 0) atomicAdd(&p.expert_cnt[i], hist[i]);
+    }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -546,6 +552,9 @@ struct RowArgs {
     int32_t* seg_cnt; int32_t* seg_off;
     int32_t* unit_cnt; int32_t* unit_off; int32_t* n_rows;
     int32_t* row_token; float* row_weight; int32_t* token_rows;
+    const int32_t* block_hist; int n_hist_blocks, m_pad;   // small batches: per-block expert counts of the gate
+    int32_t* expert_cnt_out;                               // ... and where their sum goes
+    TileJobs jobs;                                         // GEMM tile tables to build (jobs.n == 0: none)
 };
 
 // One bit per token of the segment in bm[u]: token has a row in unit u.
@@ -687,6 +696,7 @@ __global__ void __launch_bounds__(256) route_scatter_kernel(RowArgs p)
     if (blockIdx.x == 0) {
         for (int u = tid; u <= p.U; u += 256) p.unit_off[u] = off_s[u];
         if (tid == 0 && p.n_rows) p.n_rows[0] = off_s[p.U];
+        if (wave < p.jobs.n) build_tile_table(p.unit_cnt, off_s, p.jobs.job[wave], p.jobs.cap, lane);
     }
     if (tid < p.m) unit_s[tid] = p.expert_unit[tid];
     for (int i = tid; i < 4 * kMaxUnits; i += 256) (&bm[0][0])[i] = 0ull;
@@ -702,7 +712,6 @@ __global__ void __launch_bounds__(256) route_scatter_kernel(RowArgs p)
 // Small batches (at most 16 segments = 1024 tokens): Algorithm 1, the per-segment bitmaps, both scans and
 // the scatter in ONE block of 16 wavefronts, one segment per wavefront, everything in LDS.  Dynamic LDS:
 // bitmaps [16][U] (8 bytes) then segment offsets [16][U] (4 bytes).
-constexpr int kSmallSegs = 16;
 __global__ void __launch_bounds__(1024) route_small_kernel(RowArgs p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char rsm[];
@@ -714,7 +723,13 @@ __global__ void __launch_bounds__(1024) route_small_kernel(RowArgs p)
     unsigned long long* bm = reinterpret_cast<unsigned long long*>(rsm);                      // [16][U]
     int* segoff = reinterpret_cast<int*>(rsm + (size_t)kSmallSegs * p.U * 8);                  // [16][U]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid < p.m) cnt_s[tid] = p.expert_cnt[tid];
+    if (tid < p.m) {
+        // cnt_i: the sum of the gate blocks' counts (in block order; integers, so any order gives the same)
+        int c = 0;
+        for (int b = 0; b < p.n_hist_blocks; ++b) c += p.block_hist[(size_t)b * p.m_pad + tid];
+        cnt_s[tid] = c;
+        p.expert_cnt_out[tid] = c;
+    }
     for (int i = tid; i < kSmallSegs * p.U; i += 1024) bm[i] = 0ull;
     __syncthreads();
     brownout_decide(cnt_s, s2_s, unit_s, p.m, p.way, p.threshold, p.full, tid, true, p.expert_unit, p.expert_in_s1);
@@ -752,32 +767,69 @@ __global__ void __launch_bounds__(1024) route_small_kernel(RowArgs p)
     __syncthreads();
     for (int u = tid; u <= p.U; u += 1024) p.unit_off[u] = off_s[u];
     if (tid == 0 && p.n_rows) p.n_rows[0] = off_s[p.U];
+    // the GEMM tile tables, by the last wavefronts (the first ones hold the tokens of a short batch)
+    if (15 - wave < p.jobs.n) build_tile_table(ucnt_s, off_s, p.jobs.job[15 - wave], p.jobs.cap, lane);
     if (t < p.T) scatter_token(p, unit_s, bm + (size_t)wave * p.U, off_s, segoff + wave * p.U, t, lane);
 }
 
 constexpr int kGateLds = 160 * 1024;                    // LDS of one CU (the tiled gate also holds a 1 KiB histogram)
 
-hipError_t launch_route(const Dims& D, const bf16_t* x, const float* gate_w, const float* gate_bias,
-                        double threshold, int full_brownout, const RouteBufs& R, bf16_t* gate_split,
-                        int32_t* seg_cnt, int32_t* seg_off, hipStream_t s)
+#define BMOE_GATE_TILED_ALL(X) \
+    X(4, 2, 64, 1) X(4, 2, 32, 1) X(4, 4, 64, 1) X(4, 4, 32, 1) X(4, 4, 32, 2) \
+    X(2, 2, 64, 1) X(2, 2, 32, 1) X(2, 4, 64, 1) X(2, 4, 32, 1) X(2, 4, 32, 2)
+
+hipError_t init_route_kernels()
 {
-    {
+    hipError_t e;
+#define BMOE_SET(TG_, NTH_, KB_, MT_)                                                                    \
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(gate_tiled_kernel<TG_, NTH_, KB_, MT_>),       \
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kGateLds - 1024);                \
+    if (e != hipSuccess) return e;
+    BMOE_GATE_TILED_ALL(BMOE_SET)
+#undef BMOE_SET
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(route_small_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, kSmallSegs * kMaxUnits * 12);
+}
+
+hipError_t launch_pack_gate(const float* gate_w, int m, int m_pad, int d, bf16_t* packed, hipStream_t s)
+{
+    const size_t n = (size_t)m_pad * d;
+    const int blocks = (int)std::min<size_t>((n + 255) / 256, 2048);
+    prep_kernel<<<blocks, 256, 0, s>>>(gate_w, m, m_pad, d, reinterpret_cast<unsigned short*>(packed), nullptr);
+    return hipGetLastError();
+}
+
+hipError_t launch_route(const Dims& D, const bf16_t* x, const void* gate, const float* gate_bias,
+                        double threshold, int full_brownout, const RouteBufs& R, bf16_t* gate_split,
+                        int32_t* seg_cnt, int32_t* seg_off, int32_t* gate_hist, const TileJobs& jobs, hipStream_t s)
+{
+    hipError_t e = ensure_device_init(nullptr);
+    if (e != hipSuccess) return e;
+    const bool small = D.n_seg <= kSmallSegs;            // one block routes the whole batch
+    const bool packed = D.gate_format == MOE_GATE_PACKED;
+    // Small batches: the gate blocks leave their expert counts side by side and the routing block adds them
+    // up, so nothing has to be cleared first; with a packed gate there is then no preparation launch at all.
+    if (!packed || !small) {
         ProfScope ps(MOE_STAGE_PREP, s);
-        const size_t n = (size_t)D.m_pad * D.d;
+        const size_t n = packed ? (size_t)D.m : (size_t)D.m_pad * D.d;
         const int blocks = (int)std::min<size_t>((n + 255) / 256, 2048);
-        prep_kernel<<<blocks, 256, 0, s>>>(gate_w, D.m, D.m_pad, D.d, reinterpret_cast<unsigned short*>(gate_split),
-                                           R.expert_cnt);
+        prep_kernel<<<blocks, 256, 0, s>>>(packed ? nullptr : static_cast<const float*>(gate), D.m, D.m_pad, D.d,
+                                           packed ? nullptr : reinterpret_cast<unsigned short*>(gate_split),
+                                           small ? nullptr : R.expert_cnt);
     }
     {
         ProfScope ps(MOE_STAGE_GATE, s);
         GateArgs g;
-        g.x = x; g.split = reinterpret_cast<const unsigned short*>(gate_split); g.bias = gate_bias;
+        g.x = x;
+        g.split = packed ? static_cast<const unsigned short*>(gate) : reinterpret_cast<const unsigned short*>(gate_split);
+        g.bias = gate_bias;
         g.T = D.T; g.d = D.d; g.m = D.m; g.m_pad = D.m_pad; g.K = D.K; g.score_fn = D.score_fn; g.n_stage = 3;
         const int n_tiles = D.m_pad / 16;
         g.NG = n_tiles < 4 ? n_tiles : 4;
         g.KS = std::max(1, std::min(16 / g.NG, 256 / D.m_pad));
         const int ntw = ceil_div(n_tiles, g.NG);
         g.topk_idx = R.topk_idx; g.topk_w = R.topk_w; g.expert_cnt = R.expert_cnt; g.near_tie = R.near_tie;
+        g.block_hist = small ? gate_hist : nullptr;
         // many experts and enough tokens to fill the CUs with wider token tiles: LDS-staged variant
         const int half_tiles = ceil_div(n_tiles, 2);
         const int tgw = D.T >= 64 * 192 ? 4 : (D.T >= 32 * 192 ? 2 : 0);
@@ -788,18 +840,7 @@ hipError_t launch_route(const Dims& D, const bf16_t* x, const float* gate_w, con
             g.n_stage = std::max(3, std::min(8, (kGateLds - 1024) / stage));
             const int lds = std::max(g.n_stage * stage, 16 * tgw * D.m_pad * 4);
             const int blocks = ceil_div(D.T, 16 * tgw);
-            hipError_t e = hipSuccess;
-#define BMOE_GATE_TILED(TG_, NTH_, KB_, MT_)                                                                         \
-            do {                                                                                                   \
-                static bool attr_set = false;                                                                      \
-                if (!attr_set) {                                                                                   \
-                    e = hipFuncSetAttribute(reinterpret_cast<const void*>(gate_tiled_kernel<TG_, NTH_, KB_, MT_>), \
-                                            hipFuncAttributeMaxDynamicSharedMemorySize,                            \
-                                            kGateLds - 1024);                                                      \
-                    attr_set = e == hipSuccess;                                                                    \
-                }                                                                                                  \
-                if (e == hipSuccess) gate_tiled_kernel<TG_, NTH_, KB_, MT_><<<blocks, TG_ * 128, lds, s>>>(g);     \
-            } while (0)
+#define BMOE_GATE_TILED(TG_, NTH_, KB_, MT_) gate_tiled_kernel<TG_, NTH_, KB_, MT_><<<blocks, TG_ * 128, lds, s>>>(g)
             // more than 8 expert tiles (at most 16): two token tiles per wave and a quarter of the experts
             // instead of one token tile and half of the experts
             static_assert(kMaxExperts <= 256, "a wave holds at most four expert tiles per quarter");
@@ -813,13 +854,13 @@ hipError_t launch_route(const Dims& D, const bf16_t* x, const float* gate_w, con
                 else BMOE_GATE_TILED(2, 4, 32, 2);
             }
 #undef BMOE_GATE_TILED
-            if (e != hipSuccess) return e;
         } else {
             const int blocks = ceil_div(D.T, 16);
             if (ntw == 1) gate_topk_kernel<1><<<blocks, 1024, 0, s>>>(g);
             else if (ntw == 2) gate_topk_kernel<2><<<blocks, 1024, 0, s>>>(g);
             else gate_topk_kernel<4><<<blocks, 1024, 0, s>>>(g);
         }
+        if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     RowArgs p;
     p.topk_idx = R.topk_idx; p.topk_w = R.topk_w; p.expert_cnt = R.expert_cnt;
@@ -828,15 +869,10 @@ hipError_t launch_route(const Dims& D, const bf16_t* x, const float* gate_w, con
     p.full = full_brownout; p.threshold = threshold;
     p.seg_cnt = seg_cnt; p.seg_off = seg_off; p.unit_cnt = R.unit_cnt; p.unit_off = R.unit_off; p.n_rows = R.n_rows;
     p.row_token = R.row_token; p.row_weight = R.row_weight; p.token_rows = R.token_rows;
-    if (D.n_seg <= kSmallSegs) {
+    p.block_hist = gate_hist; p.n_hist_blocks = ceil_div(D.T, 16); p.m_pad = D.m_pad; p.expert_cnt_out = R.expert_cnt;
+    p.jobs = jobs;
+    if (small) {
         ProfScope ps(MOE_STAGE_COUNT, s);
-        static bool attr_set = false;
-        if (!attr_set) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(route_small_kernel),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, kSmallSegs * kMaxUnits * 12);
-            if (e != hipSuccess) return e;
-            attr_set = true;
-        }
         route_small_kernel<<<1, 1024, (size_t)kSmallSegs * D.U * 12, s>>>(p);
         return hipGetLastError();
     }

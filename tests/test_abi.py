@@ -60,6 +60,64 @@ def test_workspace_size_grows_with_tokens_and_rejects_bad_shapes():
     assert ei.value.status == -1
 
 
+def test_a_workspace_sized_for_t_max_serves_every_smaller_batch():
+    """moe_route / moe_forward / moe_build_united / moe_distill_united take the bytes moe_workspace_size
+    gives for THEIR T (the same carving code), so a workspace sized for T_max serves every T <= T_max iff
+    the size never shrinks as T grows.  Checked for every T on small shapes and on a dense grid of T on the
+    benchmark shapes (where the number of K planes of Y, which falls as T grows, used to make it shrink)."""
+    shapes = [
+        P.make_config(4096, 14336, 8, 2, 8),                       # Mixtral
+        P.make_config(2048, 768, 128, 8, 8),                       # Qwen3-30B-A3B
+        P.make_config(7168, 2048, 256, 8, 8, 1, 2048, 1),          # DeepSeek-V3 shape
+        P.make_config(2048, 1408, 60, 4, 8, 1, 5632),              # Qwen1.5-MoE shape (shared expert of its own width)
+        P.make_config(256, 512, 8, 2, 8),
+        P.make_config(64, 64, 4, 2, 2, 2, 128),
+        B.with_packed_gate(P.make_config(4096, 14336, 8, 2, 8)),
+    ]
+    for cfg in shapes:
+        dense = cfg.d_model <= 256
+        ts = list(range(1, 2200)) if dense else sorted(set(list(range(1, 4200, 7)) + list(range(370, 400)) +
+                                                        list(range(1500, 1560)) + [4096, 8192, 16384, 20000]))
+        prev = 0
+        for T in ts:
+            n = P.workspace_size(cfg, T)
+            assert n >= prev, f"workspace shrinks from {prev} to {n} at T={T} (d={cfg.d_model}, m={cfg.n_experts})"
+            assert n % 256 == 0
+            prev = n
+    # the trainer's workspace contains the forward workspace for the same number of tokens
+    cfg = P.make_config(4096, 14336, 8, 2, 8)
+    n = C.c_size_t(0)
+    for n_calib in (64, 384, 512, 1024):
+        assert P.lib().moe_distill_workspace_size(C.byref(cfg), n_calib, C.byref(n)) == 0
+        assert n.value >= P.workspace_size(cfg, n_calib)
+
+
+def test_packed_gate_size_and_validation():
+    L = P.lib()
+    cfg = P.make_config(256, 512, 8, 2, 8)
+    n = C.c_size_t(0)
+    assert L.moe_gate_packed_size(C.byref(cfg), C.byref(n)) == 0
+    assert n.value == 3 * 16 * 256 * 2                       # three bf16 pieces of the 16-row padded matrix
+    assert L.moe_gate_packed_size(C.byref(cfg), None) == -1
+    assert L.moe_pack_gate(C.byref(cfg), None, _fake(), n.value, None) == -1
+    assert L.moe_pack_gate(C.byref(cfg), _fake(), None, n.value, None) == -1
+    assert L.moe_pack_gate(C.byref(cfg), _fake(), _fake(0x20000), n.value - 1, None) == -4
+    assert L.moe_pack_gate(C.byref(cfg), _fake(0x10004), _fake(0x20000), n.value, None) == -3
+    bad = P.make_config(256, 512, 8, 2, 8, gate_format=5)
+    with pytest.raises(P.MoeError) as ei:
+        P.workspace_size(bad, 64)
+    assert ei.value.status == -1
+    # a packed gate needs no room for the pieces in the workspace
+    assert P.workspace_size(B.with_packed_gate(cfg), 64) < P.workspace_size(cfg, 64)
+
+
+def test_activations_beyond_32_bit_offsets_are_refused():
+    cfg = P.make_config(4096, 14336, 8, 2, 8)
+    with pytest.raises(P.MoeError) as ei:
+        P.workspace_size(cfg, 600000)                        # T*d*2 bytes >= 4 GiB
+    assert ei.value.status == -5
+
+
 def _fake(addr=0x10000):
     return C.c_void_p(addr)
 

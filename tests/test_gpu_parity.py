@@ -55,6 +55,19 @@ SMALL = {
     # ... and more tiles than blocks in GEMM1: one round of whole tiles, then the remainder cut eight ways
     "k_split_tail_after_full_round": (WL.LayerConfig("k_split_tail_full", T=2200, d=4096, F=4096, m=2, K=2, way=2),
                                       [0.0]),
+    # 384 expected rows per expert and more: the persistent 256-row kernel on strongly skewed loads (hot experts
+    # of many tiles beside cold ones of a few rows), with and without a shared expert in the same launch
+    "skewed_256_row_tiles": (WL.LayerConfig("skewed_256_row_tiles", T=2600, d=256, F=384, m=6, K=1, way=3, zipf_s=2.0),
+                             [1.0, 0.6]),
+    "skewed_with_shared": (WL.LayerConfig("skewed_with_shared", T=1700, d=128, F=256, m=4, K=2, way=2, n_shared=1,
+                                            F_s=256, zipf_s=1.5), [1.0, 0.5]),
+    # shared experts of their own width in a batch whose routed rows are few enough for K planes of Y: the
+    # persistent 256-row kernel runs the shared rows with the K split over the planes ...
+    "shared_own_width_k_planes": (WL.LayerConfig("shared_own_width_k_planes", T=600, d=128, F=2048, m=16, K=2, way=4,
+                                                 n_shared=1, F_s=1024), [1.0, 0.5]),
+    # ... also when the shared experts have fewer k tiles than there are planes (empty slices: zeros)
+    "shared_narrower_than_planes": (WL.LayerConfig("shared_narrower_than_planes", T=600, d=128, F=2048, m=16, K=2,
+                                                   way=4, n_shared=1, F_s=64), [1.0]),
     # the largest K and number of shared experts the library accepts
     "max_topk_max_shared": (WL.LayerConfig("max_topk_max_shared", T=48, d=64, F=64, m=64, K=32, way=8, n_shared=8,
                                            F_s=64), [1.0, 0.5]),
@@ -81,31 +94,20 @@ def test_route_and_forward(cfg, thr, full):
     united = tuple(a.to(DEV) for a in united_cpu)
     out = P.moe_forward(c, Lg.x, Lg.gate_w, Lg.gate_b, Lg.experts, united, Lg.shared, thr, full)
     out_r = P.moe_forward(c, Lg.x, None, None, Lg.experts, united, Lg.shared, route=R)
+    # the gate matrix repacked once instead of on every call: same bits everywhere
+    cp, gp = P.with_packed_gate(c), P.pack_gate(c, Lg.gate_w)
+    Rp = P.moe_route(cp, Lg.x, gp, Lg.gate_b, thr, full)
+    out_p = P.moe_forward(cp, Lg.x, gp, Lg.gate_b, Lg.experts, united, Lg.shared, thr, full)
     torch.cuda.synchronize()
+    for f in ("topk_idx", "topk_w", "expert_cnt", "expert_unit", "unit_cnt", "unit_off", "token_rows", "n_rows"):
+        assert torch.equal(getattr(R, f), getattr(Rp, f)), f
+    assert torch.equal(out, out_p)
     want = O.forward_tokens(npf(L.x), idx, w, unit, cfg.way, npf(L.experts), npf(united_cpu), npf(L.shared))
     got = npf(out)
     assert np.isfinite(got).all()
     e = rel_err(got, want)
     assert e <= OUT_TOL, f"max relative error {e}"
     assert torch.equal(out, out_r), "forward with a precomputed route must equal routing internally"
-
-
-def test_register_staged_kernel_for_wide_offsets(monkeypatch):
-    """The 256-row kernel that stands in when a byte offset into the gathered activations does not fit 32
-    bits (forced here through its switch: such a tensor would not fit a test)."""
-    cfg, thrs = SMALL["multi_tile"]
-    L, Lg = _layer(cfg)
-    c = P.config_of(cfg)
-    united_cpu = WL.make_random_united(cfg, 0, "cpu")
-    united = tuple(a.to(DEV) for a in united_cpu)
-    monkeypatch.setenv("BROWNOUT_MOE_RS", "1")
-    for thr in thrs:
-        ref = oracle_route(L, cfg, thr)
-        out = P.moe_forward(c, Lg.x, Lg.gate_w, Lg.gate_b, Lg.experts, united, Lg.shared, thr)
-        torch.cuda.synchronize()
-        want = O.forward_tokens(npf(L.x), ref.topk_idx, ref.topk_w, ref.expert_unit, cfg.way, npf(L.experts),
-                                npf(united_cpu), npf(L.shared))
-        assert rel_err(npf(out), want) <= OUT_TOL
 
 
 def test_workspace_reuse_and_side_stream():
@@ -133,6 +135,73 @@ def test_workspace_reuse_and_side_stream():
     assert torch.equal(b, fresh_small)
 
 
+def test_hand_made_rows_hot_and_cold_units_side_by_side():
+    """Row lists brought by the caller (moe_forward with route != NULL; the tile table is then built by the
+    stand-alone kernel): units of 3000, 1, 129, 64, 65, 0, 257 and 128 rows in one batch, so one grouped launch
+    holds a unit of many whole tiles, ragged last tiles of every fill, a one-row unit and an empty one."""
+    torch.cuda.set_device(0)
+    counts = [3000, 1, 129, 64, 65, 0, 257, 128]
+    m, K = len(counts), 1
+    T = sum(counts)
+    cfg = WL.LayerConfig("hand_made", T=T, d=256, F=320, m=m, K=K, way=4)
+    L, Lg = _layer(cfg)
+    c = P.config_of(cfg)
+    rng = np.random.default_rng(7)
+    idx = np.repeat(np.arange(m, dtype=np.int32), counts)
+    rng.shuffle(idx)
+    idx = idx.reshape(T, 1)
+    w = rng.uniform(0.25, 1.0, size=(T, 1)).astype(np.float32)
+    unit = np.arange(m, dtype=np.int32)
+    rows = O.build_rows(idx, w, m, cfg.way, 0, unit)
+    assert rows.unit_cnt[:m].tolist() == counts
+    R = P.alloc_route_out(c, T, DEV)
+    put = lambda dst, a: dst[:len(a)].copy_(torch.from_numpy(np.ascontiguousarray(a)).to(DEV))
+    put(R.expert_unit, unit); put(R.unit_cnt, rows.unit_cnt); put(R.unit_off, rows.unit_off)
+    put(R.row_token, rows.row_token); put(R.row_weight, rows.row_weight)
+    R.token_rows.copy_(torch.from_numpy(rows.token_rows).to(DEV))
+    out = P.moe_forward(c, Lg.x, None, None, Lg.experts, None, None, route=R)
+    torch.cuda.synchronize()
+    want = O.forward_tokens(npf(L.x), idx, w, unit, cfg.way, npf(L.experts))
+    got = npf(out)
+    assert np.isfinite(got).all()
+    per_unit = {u: rel_err(got[idx[:, 0] == u], want[idx[:, 0] == u]) for u in range(m) if counts[u]}
+    assert max(per_unit.values()) <= OUT_TOL, per_unit
+
+
+def test_first_call_of_a_process_can_be_the_captured_one():
+    """A fresh process sizes its workspace (which performs the library's per-device set-up) and then makes its
+    very FIRST moe_forward under stream capture; the replayed graph must give the eager result."""
+    import subprocess
+    import sys
+    code = r'''
+import sys, torch
+sys.path.insert(0, %r)
+import paper_2507_17133_amd as P
+from paper_2507_17133_amd import workloads as WL
+torch.cuda.set_device(0)
+for name, cfg in (("small", WL.LayerConfig("g", T=600, d=128, F=256, m=8, K=2, way=4)),
+                  ("tiled_gate_and_256_row_tiles", WL.LayerConfig("g2", T=6200, d=128, F=64, m=96, K=4, way=8, zipf_s=1.0, n_shared=1, F_s=64))):
+    L = WL.make_layer(cfg, 3, "cuda")
+    united = WL.make_random_united(cfg, 0, "cuda")
+    c = P.config_of(cfg)
+    ws = P.alloc_workspace(c, cfg.T)                       # moe_workspace_size: per-device set-up happens here
+    out = torch.empty_like(L.x)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        P.moe_forward(c, L.x, L.gate_w, L.gate_b, L.experts, united, L.shared, 0.5, out=out, workspace=ws)
+    g.replay(); torch.cuda.synchronize()
+    first = out.clone()
+    eager = P.moe_forward(c, L.x, L.gate_w, L.gate_b, L.experts, united, L.shared, 0.5)
+    g.replay(); torch.cuda.synchronize()
+    assert torch.equal(first, eager) and torch.equal(out, eager), name
+print("captured-first ok")
+''' % (str(__import__("pathlib").Path(__file__).resolve().parents[1]),)
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0 and "captured-first ok" in r.stdout, r.stdout + r.stderr
+
+
 @pytest.mark.parametrize("name", ["mid_tile", "k_split_tail_gemm2"])
 def test_forward_replays_from_a_hip_graph(name):
     """moe_forward launches kernels only, so a caller can capture it; every replay, with eager work on other
@@ -150,7 +219,7 @@ def test_forward_replays_from_a_hip_graph(name):
     def eager(x):
         return P.moe_forward(c, x, Lg.gate_w, Lg.gate_b, Lg.experts, united, Lg.shared, thr)
 
-    want1, want2 = eager(Lg.x), eager(Lg2.x)           # also the warm-up: one-time attribute calls happen here
+    want1, want2 = eager(Lg.x), eager(Lg2.x)
     torch.cuda.synchronize()
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g):
@@ -267,6 +336,19 @@ def test_build_united_mean_and_loss():
     for k in range(3):
         assert torch.equal(u1[k], Lg.experts[k])
     assert (npf(l1) == 0).all()
+
+
+def test_build_united_loss_with_a_large_calibration_batch():
+    """512 calibration tokens: the FFNs behind the loss run in 256-row tiles, and the workspace the binding
+    allocates (moe_workspace_size for 512 tokens) must be enough."""
+    cfg = WL.LayerConfig("united512", T=512, d=128, F=256, m=4, K=2, way=2)
+    L, Lg = _layer(cfg)
+    c = P.config_of(cfg)
+    calib_cpu = WL.make_activations(cfg, 0, "cpu", name="calib", n=512)
+    united, loss = P.moe_build_united(c, Lg.experts, calib_cpu.to(DEV))
+    torch.cuda.synchronize()
+    ref_loss = O.united_loss(npf(calib_cpu), cfg.way, npf(L.experts), npf(united))
+    assert np.allclose(npf(loss), ref_loss, rtol=3e-2, atol=1e-6), (npf(loss), ref_loss)
 
 
 def test_identical_group_members_hide_brownout():

@@ -198,3 +198,62 @@ def test_united_loss_decomposition():
     assert abs(loss[2]) < 1e-20                                           # single-member group: student == teacher
     ident = O.united_loss(calib, 1, L["experts"], L["experts"])
     assert (ident == 0).all()
+
+
+def _explicit_layer(x, idx, w, unit, m, experts, united, shared, add_residual):
+    """The layer equation written out with torch fp64 matmuls, token by token (independent of the C file)."""
+    def f(xr, W, i):
+        return _dense_swiglu(xr[None, :], W[0][i], W[1][i], W[2][i])[0]
+    out = np.zeros(x.shape, np.float64)
+    for t in range(x.shape[0]):
+        if add_residual:
+            out[t] += x[t]
+        for s in range(0 if shared is None else shared[0].shape[0]):
+            out[t] += f(x[t], shared, s)
+        for j in range(idx.shape[1]):
+            u = unit[idx[t, j]]
+            if u < 0:
+                continue
+            out[t] += float(w[t, j]) * (f(x[t], experts, u) if u < m else f(x[t], united, u - m))
+    return out
+
+
+@pytest.mark.parametrize("full,residual", [(False, False), (False, True), (True, False)])
+def test_forward_tokens_lazy_equals_forward_tokens(full, residual):
+    """The helper that evaluates the layer equation for sampled tokens of layers too large to hold as float
+    arrays (weights fetched per FFN) against the plain evaluation, on a layer where every kind of term
+    occurs: experts served by themselves, several TopK entries of a token delegated to the SAME united
+    expert, dropped experts (full brownout), two shared experts, the residual."""
+    m, K, way, ns = 8, 4, 4, 2
+    L = _layer(T=40, d=32, F=40, m=m, K=K, seed=11, n_shared=ns, Fs=24)
+    rng = np.random.default_rng(5)
+    un = tuple((rng.standard_normal(a[:2].shape) / 6).astype(np.float32) for a in L["experts"])
+    r = O.route(L["x"], L["gw"], None, K, way, 0.35, full, 0, ns)
+    unit = r.expert_unit
+    if full:
+        assert (unit < 0).any()
+    else:
+        assert (unit >= m).any() and (unit < m).any()
+        # some token has two of its TopK experts delegated to one united expert
+        assert any(len(set(u for u in unit[r.topk_idx[t]] if u >= m)) < sum(unit[r.topk_idx[t]] >= m)
+                   for t in range(40))
+    want = O.forward_tokens(L["x"], r.topk_idx, r.topk_w, unit, way, L["experts"], un, L["shared"],
+                            add_residual=residual)
+    src = {"expert": L["experts"], "united": un, "shared": L["shared"]}
+    calls = []
+
+    def get(kind, i):
+        calls.append((kind, i))
+        return tuple(a[i] for a in src[kind])
+    toks = np.array([0, 3, 4, 17, 18, 39, 25], np.int64)
+    got = O.forward_tokens_lazy(L["x"][toks], r.topk_idx[toks], r.topk_w[toks], unit, m, get, ns, residual)
+    assert np.allclose(got, want[toks], rtol=1e-6, atol=1e-7)            # forward_tokens returns float
+    exact = _explicit_layer(L["x"], r.topk_idx, r.topk_w, unit, m, L["experts"], un, L["shared"], residual)
+    assert np.allclose(got, exact[toks], rtol=1e-9, atol=1e-11)
+    assert len(calls) == len(set(calls))                                  # one fetch per distinct FFN
+    # a wrong unit -> weights lookup must be visible: shift the united index by one
+    def get_wrong(kind, i):
+        return tuple(a[(i + 1) % a.shape[0]] if kind == "united" else a[i] for a in src[kind])
+    if not full:
+        bad = O.forward_tokens_lazy(L["x"][toks], r.topk_idx[toks], r.topk_w[toks], unit, m, get_wrong, ns, residual)
+        assert not np.allclose(bad, exact[toks], rtol=1e-3, atol=1e-4)
