@@ -193,6 +193,24 @@ moe_status moe_route(const moe_config *cfg, const void *x, int32_t T, const void
                      const moe_route_out *out, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * moe_route for callers that cannot allocate device memory or hand over a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * allocation): same arguments without the workspace, same results bit for bit.  Its
+ * work space is a fixed 8 MiB array inside the library's device image (one per
+ * GPU, held until the process ends); fields of `out` left NULL live there too.
+ * The call allocates and frees nothing (profiling, moe_profile_enable, must be off:
+ * it creates events).  A batch whose routing work space exceeds 8 MiB is rejected
+ * with MOE_ERR_WORKSPACE before anything is launched; the need is about
+ * T*(K+N_s)*12 + T*K*8 + T/64*U*8 bytes, plus 6*16*ceil(m/16)*d for an unpacked gate
+ * (pack it with moe_pack_gate to save that).  All calls on one GPU share the array:
+ * two such calls whose work overlaps in time (different streams) race; calls on one
+ * stream are safe, and nothing an earlier call left in the array is read.
+ */
+moe_status moe_route_static(const moe_config *cfg, const void *x, int32_t T, const void *gate_w,
+                            const float *gate_bias, double threshold, int32_t use_full_brownout,
+                            const moe_route_out *out, void *stream);
+
+/*
  * The layer equation:
  *   out_t = [x_t] + sum_s FFN^(s)_s(x_t) + sum_i p_{i,t} FFN^(r)_i(x_t) + sum_i q_{i,t} FFN^(u)_{floor(i/way)}(x_t)
  * out [T][d] bf16.  route == NULL: routing is computed internally exactly as

@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libbrownout_moe.so")
 MOE_OK = 0
 STAGES = ("prep", "gate", "count", "scan", "scatter", "tiles", "gemm1", "gemm2", "combine")
 EXPORTS = ("moe_status_string", "moe_last_hip_error", "moe_init", "moe_workspace_size", "moe_gate_packed_size",
-           "moe_pack_gate", "moe_build_united", "moe_route", "moe_forward",
+           "moe_pack_gate", "moe_build_united", "moe_route", "moe_route_static", "moe_forward",
            "moe_distill_workspace_size", "moe_distill_united", "moe_profile_enable", "moe_profile_collect",
            "moe_latency_p90", "moe_salc_update", "moe_probe_mfma", "moe_probe_hbm_read")
 MOE_GATE_FP32, MOE_GATE_PACKED = 0, 1
@@ -76,6 +76,9 @@ def lib():
         L.moe_gate_packed_size.argtypes = [C.POINTER(moe_config), C.POINTER(C.c_size_t)]
         L.moe_pack_gate.restype = C.c_int32
         L.moe_pack_gate.argtypes = [C.POINTER(moe_config), C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.moe_route_static.restype = C.c_int32
+        L.moe_route_static.argtypes = [C.POINTER(moe_config), C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_double,
+                                       C.c_int32, C.POINTER(moe_route_out), C.c_void_p]
         L.moe_build_united.restype = C.c_int32
         L.moe_build_united.argtypes = [C.POINTER(moe_config), C.POINTER(moe_ffn_weights), C.POINTER(moe_ffn_weights),
                                        C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
@@ -235,6 +238,19 @@ def _check_gate(cfg: moe_config, gate_w):
         assert gate_w.dtype == torch.uint8
     else:
         assert gate_w.dtype == torch.float32 and tuple(gate_w.shape) == (cfg.n_experts, cfg.d_model)
+
+
+def moe_route_static(cfg: moe_config, x, gate_w, gate_bias, threshold: float, use_full_brownout: bool,
+                     out: RouteOut, stream=None) -> RouteOut:
+    """moe_route on the library's own fixed scratch: no workspace argument; `out` is the caller's (allocate it
+    beforehand: this call allocates nothing)."""
+    T = x.shape[0]
+    assert x.is_cuda and x.dtype == torch.bfloat16 and x.is_contiguous() and x.shape[1] == cfg.d_model
+    _check_gate(cfg, gate_w)
+    st = out.as_struct()
+    _check(lib().moe_route_static(C.byref(cfg), _ptr(x), T, _ptr(gate_w), _ptr(gate_bias), float(threshold),
+                                  1 if use_full_brownout else 0, C.byref(st), _stream(stream)), "moe_route_static")
+    return out
 
 
 def moe_forward(cfg: moe_config, x, gate_w, gate_bias, experts, united=None, shared=None, threshold: float = 1.0,

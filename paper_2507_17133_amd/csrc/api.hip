@@ -10,6 +10,12 @@
 #include <string>
 #include <vector>
 
+// Scratch of moe_route_static (callers that cannot allocate): routing work space of a stated, modest size
+// that lives in the library's own device image.  In host code this name is only a handle for
+// hipGetSymbolAddress; the device address is looked up once per device in ensure_device_init.
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace bmoe {
 
 constexpr int kMixedRows = 384;      // expected rows per unit from which 256-row tiles are used
@@ -38,6 +44,7 @@ const Tuning& tuning()
 static std::mutex g_init_mutex;
 static bool g_init_done[kMaxDevices] = {false};
 static DeviceInfo g_dev_info[kMaxDevices];
+static void* g_scratch_ptr[kMaxDevices] = {nullptr};
 
 hipError_t ensure_device_init(DeviceInfo* info)
 {
@@ -52,11 +59,21 @@ hipError_t ensure_device_init(DeviceInfo* info)
         if ((e = init_route_kernels()) != hipSuccess) return e;
         int n_cu = 0;
         if ((e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev)) != hipSuccess) return e;
+        void* sp = nullptr;
+        if ((e = hipGetSymbolAddress(&sp, HIP_SYMBOL(scratch))) != hipSuccess) return e;
         g_dev_info[dev].n_cu = n_cu;
+        g_scratch_ptr[dev] = sp;
         g_init_done[dev] = true;
     }
     if (info) *info = g_dev_info[dev];
     return hipSuccess;
+}
+
+static void* static_scratch_of_current_device()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    return g_scratch_ptr[dev];
 }
 
 static thread_local std::string g_hip_error;
@@ -133,7 +150,7 @@ static int64_t y_rows_bound(const Dims& D)
 }
 
 // Every piece grows (weakly) with T, so the total does: moe_workspace_size(T_max) covers every T <= T_max.
-// The routing pieces come first: they are all that routing alone needs.
+// The routing pieces come first: carve_route_only() is the prefix moe_route_static needs.
 static void carve_route_pieces(const Dims& D, Workspace& W, size_t& o)
 {
     auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes, 256); return at; };
@@ -393,6 +410,34 @@ moe_status moe_route(const moe_config* cfg, const void* x, int32_t T, const void
                                 at<int32_t>(workspace, W.seg_cnt), at<int32_t>(workspace, W.seg_off),
                                 at<int32_t>(workspace, W.gate_hist), none, s);
     if (e != hipSuccess) return hip_fail(e, "moe_route");
+    return MOE_OK;
+}
+
+moe_status moe_route_static(const moe_config* cfg, const void* x, int32_t T, const void* gate_w,
+                            const float* gate_bias, double threshold, int32_t use_full_brownout,
+                            const moe_route_out* out, void* stream)
+{
+    moe_status st = check_route_args(cfg, x, T, gate_w, gate_bias, threshold, out);
+    if (st != MOE_OK) return st;
+    const Dims D = make_dims(*cfg, T);
+    Workspace W;
+    size_t need = 0;
+    carve_route_pieces(D, W, need);
+    if (need > kStaticScratchBytes) return MOE_ERR_WORKSPACE;          // beyond the stated maximum
+    hipError_t e = ensure_device_init(nullptr);                          // first call on this device: looks the scratch up
+    if (e != hipSuccess) return hip_fail(e, "moe_route_static/init");
+    void* sp = static_scratch_of_current_device();
+    if (!sp) return hip_fail(hipErrorInvalidDevice, "moe_route_static/scratch");
+    const RouteBufs R = resolve_route(out, sp, W);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    TileJobs none;
+    none.n = 0; none.cap = 0;
+    // everything the kernels read from the scratch they write first in the same call (counters are cleared by
+    // the first kernel), so what an earlier call left there does not matter
+    e = launch_route(D, static_cast<const bf16_t*>(x), gate_w, gate_bias, threshold, use_full_brownout ? 1 : 0, R,
+                     at<bf16_t>(sp, W.gate_split), at<int32_t>(sp, W.seg_cnt), at<int32_t>(sp, W.seg_off),
+                     at<int32_t>(sp, W.gate_hist), none, s);
+    if (e != hipSuccess) return hip_fail(e, "moe_route_static");
     return MOE_OK;
 }
 

@@ -118,6 +118,24 @@ def test_activations_beyond_32_bit_offsets_are_refused():
     assert ei.value.status == -5
 
 
+def test_route_static_validates_and_rejects_batches_beyond_its_scratch():
+    L = P.lib()
+    cfg = P.make_config(256, 512, 8, 2, 8)
+    ro = B.moe_route_out()
+
+    def rs(x=_fake(), T=64, gw=_fake(0x20000), thr=1.0, out=C.byref(ro), c=cfg):
+        return L.moe_route_static(C.byref(c), x, T, gw, None, thr, 0, out, None)
+
+    assert rs(thr=1.5) == -1
+    assert rs(T=0) == -1
+    assert rs(x=None) == -1
+    assert rs(out=None) == -1
+    assert rs(x=_fake(0x10004)) == -3
+    big = P.make_config(7168, 2048, 256, 8, 8, 1, 2048, 1)     # unpacked gate alone is 11 MB: beyond the 8 MiB
+    assert rs(c=big, T=64) == -4
+    assert rs(T=200000) == -4                                 # row lists beyond the 8 MiB
+
+
 def _fake(addr=0x10000):
     return C.c_void_p(addr)
 
