@@ -34,6 +34,8 @@ def main():
     ap.add_argument("--way", type=int, default=None)
     ap.add_argument("--tokens", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode", action="store_true",
+                    help="default workload only: skip the decode-sized sub-record (mixtral_decode at f = 0 and f = 1)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=None)
     ap.add_argument("--stages", action="store_true", help="also print a per-kernel time breakdown to stderr")
     ap.add_argument("--sweep", action="store_true",
@@ -79,81 +81,14 @@ def main():
     if args.tokens is not None:
         cfg = cfg.with_(T=args.tokens)
     f = cfg.brownout_fractions[0] if args.fraction is None else args.fraction
-    threshold = 1.0 - f
-    c = P.config_of(cfg)
-
-    t0 = time.time()
-    L = WL.make_layer(cfg, 0, dev)
-    united, _ = P.moe_build_united(c, L.experts)
-    ws = P.alloc_workspace(c, cfg.T, dev)
-    out = torch.empty((cfg.T, cfg.d), dtype=torch.bfloat16, device=dev)
-    R = P.moe_route(c, L.x, L.gate_w, L.gate_b, threshold, workspace=ws)
-    torch.cuda.synchronize()
-    n_rows = int(R.n_rows.item())
-    unit_cnt = R.unit_cnt.cpu().numpy()
-    expert_cnt = R.expert_cnt.cpu().numpy()
-    n_shared_rows = cfg.T * cfg.n_shared
-    n_routed_rows = n_rows - n_shared_rows
-    active_units = int((unit_cnt > 0).sum())
-    united_rows_before_merge = int(expert_cnt[(R.expert_unit.cpu().numpy() >= cfg.m)].sum())
-    log(f"[setup {time.time()-t0:.1f}s] {cfg.name}: T={cfg.T} d={cfg.d} F={cfg.F} m={cfg.m} K={cfg.K} way={cfg.way} "
-        f"threshold={threshold:.2f} rows={n_rows} active_units={active_units}/{len(unit_cnt)}")
-    log(f"  expert load (tokens): max={expert_cnt.max()} mean={expert_cnt.mean():.1f} min={expert_cnt.min()} "
-        f"units with <16 rows: {int(((unit_cnt > 0) & (unit_cnt < 16)).sum())}; realised brownout fraction "
-        f"{united_rows_before_merge / float(cfg.T * cfg.K):.3f} (asked {f:.2f})")
+    m = measure(cfg, f, args.steps, args.warmup, dev, default_shape=args.fraction is None and args.way is None
+                and args.tokens is None)
+    L, united, c, gate, ws, out, threshold = m["L"], m["united"], m["c"], m["gate"], m["ws"], m["out"], m["threshold"]
+    line_cfg = m["line_cfg"]
+    roofline, ms_per_step, tokens_per_s = m["roofline"], m["ms_per_step"], m["tokens_per_s"]
 
     def step():
-        P.moe_forward(c, L.x, L.gate_w, L.gate_b, L.experts, united, L.shared, threshold, False, None, out, ws)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    P.profile_enable(["gemm1"])          # two HIP events per step around the dominant kernel, on its stream
-    t1 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    t2 = time.perf_counter()
-    prof = P.profile_collect()
-    P.profile_disable()
-    ms_per_step = (t2 - t1) * 1e3 / args.steps
-    tokens_per_s = cfg.T * args.steps / (t2 - t1)
-
-    # GEMM1 time per step (a layer whose shared experts have their own width runs GEMM1 twice per step)
-    gemm1_ms = prof["gemm1"][0] / args.steps
-    # algorithmic flops of GEMM1 per launch: rows x (W1 and W3) : 2*2*d*F per row (shared rows with their own F)
-    flops_gemm1 = 4.0 * cfg.d * (cfg.F * n_routed_rows + cfg.F_s * n_shared_rows)
-    flops_step = 6.0 * cfg.d * (cfg.F * n_routed_rows + cfg.F_s * n_shared_rows) + 2.0 * cfg.T * cfg.d * cfg.m
-    # algorithmic bytes per step: x in, out, gate, weights of the ACTIVE units only
-    unit_bytes = np.where(np.arange(len(unit_cnt)) < cfg.m + cfg.G, 3 * cfg.d * cfg.F * 2, 3 * cfg.d * cfg.F_s * 2)
-    bytes_step = 2 * cfg.T * cfg.d * 2 + cfg.d * cfg.m * 4 + int(unit_bytes[unit_cnt > 0].sum())
-    t_mfma = flops_step / (PEAK_BF16_TFLOPS * 1e12)
-    t_hbm = bytes_step / (PEAK_HBM_GBS * 1e9)
-    hbm_bound = t_hbm > t_mfma
-    if hbm_bound:
-        # weight streaming dominates: price GEMM1 by the bytes it must read (W1, W3 of active units + gathered x)
-        g1_bytes = int((unit_bytes[unit_cnt > 0] * 2 // 3).sum()) + n_rows * cfg.d * 2 + n_rows * cfg.F * 2
-        achieved = g1_bytes / (gemm1_ms * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                    "frac": achieved / PEAK_HBM_GBS, "traffic": None}
-    else:
-        achieved = flops_gemm1 / (gemm1_ms * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                    "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None}
-    # with 256-row tiles GEMM1 is two launches (the GEMM kernel, whose extra blocks take the pieces of the tiles
-    # left over after its last full round, and the sum of their K slices): both are inside the timed interval
-    roofline["kernel"] = "GEMM1 (ffn_gemm_*_kernel<SWIGLU> and, with 256-row tiles, gemm_tail_sum_kernel)"
-    roofline["kernel_ms"] = gemm1_ms
-    # HBM bytes of one GEMM1 launch as counted by rocprofv3 (FETCH_SIZE + WRITE_SIZE, scaled by a copy
-    # probe): taken from the committed profile summary of this workload, if there is one
-    tpath = os.path.join(ROOT, "profiles", f"moe_forward_{cfg.name}.txt")
-    if os.path.exists(tpath) and args.fraction is None and args.way is None and args.tokens is None:
-        for ln in open(tpath):
-            if ln.startswith("gemm1_hbm_bytes_per_launch"):
-                roofline["traffic"] = float(ln.split("=")[1].split()[0])
-    log(f"  step {ms_per_step:.3f} ms  -> {tokens_per_s/1e6:.3f} M tok/s; layer roofline time "
-        f"{max(t_mfma, t_hbm)*1e3:.3f} ms ({'HBM' if hbm_bound else 'MFMA'}-bound) -> whole-step fraction "
-        f"{max(t_mfma, t_hbm)*1e3/ms_per_step:.3f}; GEMM1 {gemm1_ms:.3f} ms")
+        P.moe_forward(c, L.x, gate, L.gate_b, L.experts, united, L.shared, threshold, False, None, out, ws)
 
     if args.stages:
         P.profile_enable()
@@ -187,15 +122,15 @@ def main():
             thr = i / 10.0
             res = []
             for full in (False, True):
-                Rs = P.moe_route(c, L.x, L.gate_w, L.gate_b, thr, full, workspace=ws)
+                Rs = P.moe_route(c, L.x, gate, L.gate_b, thr, full, workspace=ws)
                 torch.cuda.synchronize()
                 rows_s, act_s = int(Rs.n_rows.item()), int((Rs.unit_cnt > 0).sum().item())
                 for _ in range(3):
-                    P.moe_forward(c, L.x, L.gate_w, L.gate_b, L.experts, united, L.shared, thr, full, None, out, ws)
+                    P.moe_forward(c, L.x, gate, L.gate_b, L.experts, united, L.shared, thr, full, None, out, ws)
                 torch.cuda.synchronize()
                 ts = time.perf_counter()
                 for _ in range(10):
-                    P.moe_forward(c, L.x, L.gate_w, L.gate_b, L.experts, united, L.shared, thr, full, None, out, ws)
+                    P.moe_forward(c, L.x, gate, L.gate_b, L.experts, united, L.shared, thr, full, None, out, ws)
                 torch.cuda.synchronize()
                 res.append(((time.perf_counter() - ts) * 100.0, rows_s, act_s))
             log(f"    {thr:.1f}   {res[0][0]:8.3f} ({res[0][1]} rows, {res[0][2]} units)   {res[1][0]:8.3f} ({res[1][1]} rows, {res[1][2]} units)")
@@ -210,11 +145,11 @@ def main():
         t_of = []
         for thr in thr_grid:
             for _ in range(3):
-                P.moe_forward(c, L.x, L.gate_w, L.gate_b, L.experts, united, L.shared, thr, False, None, out, ws)
+                P.moe_forward(c, L.x, gate, L.gate_b, L.experts, united, L.shared, thr, False, None, out, ws)
             torch.cuda.synchronize()
             ts = time.perf_counter()
             for _ in range(10):
-                P.moe_forward(c, L.x, L.gate_w, L.gate_b, L.experts, united, L.shared, thr, False, None, out, ws)
+                P.moe_forward(c, L.x, gate, L.gate_b, L.experts, united, L.shared, thr, False, None, out, ws)
             torch.cuda.synchronize()
             t_of.append((time.perf_counter() - ts) / 10.0 * args.salc_layers)
         tau = lambda thr: float(np.interp(thr, thr_grid, t_of))
@@ -241,15 +176,15 @@ def main():
         # layer output before and after the training.
         calib = WL.make_activations(cfg, 1, dev, name="calib", n=args.distill_tokens)
         lr = 0.02 / float(np.sqrt(cfg.d))                # 2 % of the weights' standard deviation per step
-        exact = P.moe_forward(c, L.x, L.gate_w, L.gate_b, L.experts, united, L.shared, 1.0).float()
-        before = P.moe_forward(c, L.x, L.gate_w, L.gate_b, L.experts, united, L.shared, 0.0).float()
+        exact = P.moe_forward(c, L.x, gate, L.gate_b, L.experts, united, L.shared, 1.0).float()
+        before = P.moe_forward(c, L.x, gate, L.gate_b, L.experts, united, L.shared, 0.0).float()
         trained = tuple(u.clone() for u in united)
         torch.cuda.synchronize()
         ts = time.perf_counter()
-        hist = P.moe_distill_united(c, L.experts, trained, calib, args.distill_steps, lr)
+        hist = P.moe_distill_united(m["c_plain"], L.experts, trained, calib, args.distill_steps, lr)
         torch.cuda.synchronize()
         dt = time.perf_counter() - ts
-        after = P.moe_forward(c, L.x, L.gate_w, L.gate_b, L.experts, trained, L.shared, 0.0).float()
+        after = P.moe_forward(c, L.x, gate, L.gate_b, L.experts, trained, L.shared, 0.0).float()
         rel = lambda a: float(((a - exact).norm() / exact.norm()).item())
         h = hist.cpu().numpy()
         multi = [g for g in range(cfg.G) if min(cfg.m, (g + 1) * cfg.way) - g * cfg.way > 1]
@@ -279,17 +214,141 @@ def main():
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(cfg, L, united, threshold, args.cpu_sample_tokens)
 
+    # The other half of the metric: the decode-sized batch of the same layer shape (HBM-bound weight streaming),
+    # at zero brownout and with every expert delegated to the one united expert (an eighth of the weight bytes).
+    decode = None
+    if cfg.name == "mixtral_prefill" and not args.no_decode and m["default_shape"]:
+        dcfg = WL.CONFIGS["mixtral_decode"]
+        d0 = measure(dcfg, 0.0, max(args.steps, 30), args.warmup, dev, default_shape=True)
+        d1 = measure(dcfg, 1.0, max(args.steps, 30), args.warmup, dev, default_shape=False, reuse=d0)
+        decode = {"workload": dcfg.name, "T": dcfg.T, "brownout_fraction": 0.0, "ms_per_step": d0["ms_per_step"],
+                  "tokens_per_s": d0["tokens_per_s"], "route_ms": d0["route_ms"],
+                  "layer_roofline_frac": d0["layer_frac"], "bytes_min": d0["bytes_min"],
+                  "bytes_two_gemm": d0["bytes_two_gemm"], "roofline": d0["roofline"],
+                  "full_brownout_fraction_1": {"ms_per_step": d1["ms_per_step"], "tokens_per_s": d1["tokens_per_s"],
+                                               "bytes_min": d1["bytes_min"], "layer_roofline_frac": d1["layer_frac"],
+                                               "gemm1_gbs": d1["roofline"]["achieved"]}}
     line = {
         "metric": "MoE-layer tokens/s at 1 MI355X", "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": cfg.name, "T": cfg.T, "d_model": cfg.d, "d_ff": cfg.F, "n_experts": cfg.m,
-                   "top_k": cfg.K, "way": cfg.way, "n_shared": cfg.n_shared, "brownout_fraction": f,
-                   "threshold": threshold, "rows": n_rows, "active_units": active_units,
-                   "layer_roofline_frac": max(t_mfma, t_hbm) * 1e3 / ms_per_step},
-        "roofline": roofline, "cpu_baseline": cpu,
+        "config": line_cfg, "roofline": roofline, "cpu_baseline": cpu, "decode": decode,
     }
     print(json.dumps(line), flush=True)
+
+
+def measure(cfg, f, steps, warmup, dev, default_shape, reuse=None):
+    """Times `steps` moe_forward calls of one workload at brownout fraction f (inputs resident in HBM, the gate
+    matrix packed once beforehand) and prices the step and its dominant kernel against the rooflines."""
+    import numpy as np
+    import torch
+
+    import paper_2507_17133_amd as P
+    from paper_2507_17133_amd import workloads as WL
+
+    threshold = 1.0 - f
+    c_plain = P.config_of(cfg)
+    t0 = time.time()
+    if reuse is None:
+        L = WL.make_layer(cfg, 0, dev)
+        united, _ = P.moe_build_united(c_plain, L.experts)
+        gate = P.pack_gate(c_plain, L.gate_w)          # one-time repack of the gate matrix, outside the timed region
+    else:
+        L, united, gate = reuse["L"], reuse["united"], reuse["gate"]
+    c = P.with_packed_gate(c_plain)
+    ws = P.alloc_workspace(c, cfg.T, dev)
+    out = torch.empty((cfg.T, cfg.d), dtype=torch.bfloat16, device=dev)
+    R = P.moe_route(c, L.x, gate, L.gate_b, threshold, workspace=ws)
+    torch.cuda.synchronize()
+    n_rows = int(R.n_rows.item())
+    unit_cnt = R.unit_cnt.cpu().numpy()
+    expert_cnt = R.expert_cnt.cpu().numpy()
+    n_shared_rows = cfg.T * cfg.n_shared
+    n_routed_rows = n_rows - n_shared_rows
+    active_units = int((unit_cnt > 0).sum())
+    united_rows_before_merge = int(expert_cnt[(R.expert_unit.cpu().numpy() >= cfg.m)].sum())
+    log(f"[setup {time.time()-t0:.1f}s] {cfg.name}: T={cfg.T} d={cfg.d} F={cfg.F} m={cfg.m} K={cfg.K} way={cfg.way} "
+        f"threshold={threshold:.2f} rows={n_rows} active_units={active_units}/{len(unit_cnt)}")
+    log(f"  expert load (tokens): max={expert_cnt.max()} mean={expert_cnt.mean():.1f} min={expert_cnt.min()} "
+        f"units with <16 rows: {int(((unit_cnt > 0) & (unit_cnt < 16)).sum())}; realised brownout fraction "
+        f"{united_rows_before_merge / float(cfg.T * cfg.K):.3f} (asked {f:.2f})")
+
+    def step():
+        P.moe_forward(c, L.x, gate, L.gate_b, L.experts, united, L.shared, threshold, False, None, out, ws)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    P.profile_enable(["gemm1"])          # two HIP events per step around the dominant kernel, on its stream
+    t1 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    prof = P.profile_collect()
+    P.profile_disable()
+    ms_per_step = (t2 - t1) * 1e3 / steps
+    tokens_per_s = cfg.T * steps / (t2 - t1)
+    # routing alone (gate, TopK, Algorithm 1, row lists), same inputs
+    for _ in range(3):
+        P.moe_route(c, L.x, gate, L.gate_b, threshold, False, R, ws)
+    torch.cuda.synchronize()
+    t3 = time.perf_counter()
+    for _ in range(20):
+        P.moe_route(c, L.x, gate, L.gate_b, threshold, False, R, ws)
+    torch.cuda.synchronize()
+    route_ms = (time.perf_counter() - t3) * 1e3 / 20
+
+    # GEMM1 time per step (a layer whose shared experts have their own width runs GEMM1 twice per step)
+    gemm1_ms = prof["gemm1"][0] / steps
+    # algorithmic flops of GEMM1 per launch: rows x (W1 and W3) : 2*2*d*F per row (shared rows with their own F)
+    flops_gemm1 = 4.0 * cfg.d * (cfg.F * n_routed_rows + cfg.F_s * n_shared_rows)
+    flops_step = 6.0 * cfg.d * (cfg.F * n_routed_rows + cfg.F_s * n_shared_rows) + 2.0 * cfg.T * cfg.d * cfg.m
+    # algorithmic bytes per step: x in, out, gate, weights of the ACTIVE units only; and what the two-GEMM
+    # design moves on top of that: gathered x rows, H written and read, Y written and read
+    unit_bytes = np.where(np.arange(len(unit_cnt)) < cfg.m + cfg.G, 3 * cfg.d * cfg.F * 2, 3 * cfg.d * cfg.F_s * 2)
+    bytes_min = 2 * cfg.T * cfg.d * 2 + cfg.d * cfg.m * 4 + int(unit_bytes[unit_cnt > 0].sum())
+    h_bytes = 2 * (n_routed_rows * cfg.F + n_shared_rows * cfg.F_s)
+    bytes_two_gemm = bytes_min + n_rows * cfg.d * 2 + 2 * h_bytes + 2 * n_rows * cfg.d * 2
+    t_mfma = flops_step / (PEAK_BF16_TFLOPS * 1e12)
+    t_hbm = bytes_min / (PEAK_HBM_GBS * 1e9)
+    hbm_bound = t_hbm > t_mfma
+    if hbm_bound:
+        # weight streaming dominates: price GEMM1 by the bytes it must read (W1, W3 of active units + gathered x)
+        g1_bytes = int((unit_bytes[unit_cnt > 0] * 2 // 3).sum()) + n_rows * cfg.d * 2 + h_bytes
+        achieved = g1_bytes / (gemm1_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": achieved / PEAK_HBM_GBS, "traffic": None}
+    else:
+        achieved = flops_gemm1 / (gemm1_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None}
+    # with 256-row tiles GEMM1 is two launches (the GEMM kernel, whose extra blocks take the pieces of the tiles
+    # left over after its last full round, and the sum of their K slices): both are inside the timed interval
+    roofline["kernel"] = "GEMM1 (ffn_gemm_*_kernel<SWIGLU> and, with 256-row tiles, gemm_tail_sum_kernel)"
+    roofline["kernel_ms"] = gemm1_ms
+    # HBM-side bytes of one GEMM1 launch as counted by rocprofv3 (FETCH_SIZE + WRITE_SIZE, scaled by a copy
+    # probe) in a separate counter run of this workload: read from the committed summary, not measured here
+    tpath = os.path.join(ROOT, "profiles", f"moe_forward_{cfg.name}.txt")
+    roofline["traffic_source"] = None
+    if os.path.exists(tpath) and default_shape:
+        for ln in open(tpath):
+            if ln.startswith("gemm1_hbm_bytes_per_launch"):
+                roofline["traffic"] = float(ln.split("=")[1].split()[0])
+                roofline["traffic_source"] = f"profiles/moe_forward_{cfg.name}.txt (rocprofv3 counter runs, not this run)"
+    layer_frac = max(t_mfma, t_hbm) * 1e3 / ms_per_step
+    log(f"  step {ms_per_step:.3f} ms  -> {tokens_per_s/1e6:.3f} M tok/s; layer roofline time "
+        f"{max(t_mfma, t_hbm)*1e3:.3f} ms ({'HBM' if hbm_bound else 'MFMA'}-bound) -> whole-step fraction "
+        f"{layer_frac:.3f}; GEMM1 {gemm1_ms:.3f} ms ({roofline['frac']:.3f} of nominal); routing alone {route_ms:.3f} ms")
+    return {"L": L, "united": united, "c": c, "c_plain": c_plain, "gate": gate, "ws": ws, "out": out,
+            "threshold": threshold, "roofline": roofline, "ms_per_step": ms_per_step, "tokens_per_s": tokens_per_s,
+            "route_ms": route_ms, "layer_frac": layer_frac, "bytes_min": bytes_min, "bytes_two_gemm": bytes_two_gemm,
+            "default_shape": default_shape,
+            "line_cfg": {"workload": cfg.name, "T": cfg.T, "d_model": cfg.d, "d_ff": cfg.F, "n_experts": cfg.m,
+                         "top_k": cfg.K, "way": cfg.way, "n_shared": cfg.n_shared, "brownout_fraction": f,
+                         "threshold": threshold, "rows": n_rows, "active_units": active_units,
+                         "layer_roofline_frac": layer_frac, "route_ms": route_ms, "bytes_min": bytes_min,
+                         "bytes_two_gemm": bytes_two_gemm, "flops": flops_step}}
 
 
 def cpu_baseline(cfg, L, united, threshold, n_sample):
@@ -305,43 +364,62 @@ def cpu_baseline(cfg, L, united, threshold, n_sample):
     t_route = time.perf_counter() - t0
     per_token_flops = 6.0 * cfg.d * (cfg.F * cfg.K + cfg.F_s * cfg.n_shared)
     whole = cfg.m * cfg.d * cfg.F <= 6e8        # all experts fit as float arrays: tokens run in parallel
-    if n_sample is None:
-        # about 1 TFLOP of plain loops on all cores, or 100 GFLOP when rows run one at a time on one core
-        n_sample = int(max(8, min(cfg.T, (1e12 if whole else 1e11) / per_token_flops)))
-    tokens = np.linspace(0, cfg.T - 1, n_sample).astype(np.int32)
     cores = O.num_threads()
     if whole:
+        if n_sample is None:
+            n_sample = int(max(8, min(cfg.T, 1e12 / per_token_flops)))     # about 1 TFLOP of plain loops
+        tokens = np.linspace(0, cfg.T - 1, n_sample).astype(np.int32)
+        how = f"{n_sample} evenly spaced tokens"
         ex, un, sh = tuple(f32(a) for a in L.experts), tuple(f32(a) for a in united), \
             None if L.shared is None else tuple(f32(a) for a in L.shared)
         t0 = time.perf_counter()
         O.forward_tokens(x, r.topk_idx, r.topk_w, r.expert_unit, cfg.way, ex, un, sh, tokens=tokens)
         t_ffn = time.perf_counter() - t0
     else:
+        # Too large to hold as float arrays: a stratified sample (a token from every execution unit that holds
+        # rows, then evenly spaced ones, at least 256, about 0.2 TFLOP of plain loops), one FFN at a time with
+        # its sampled rows spread over the cores; the weights are fetched before the clock starts.
+        if n_sample is None:
+            n_sample = int(max(256, min(cfg.T, 2e11 / per_token_flops)))
+        rows = r.rows
+        chosen = [int(rows.row_token[int(rows.unit_off[u]) + int(rows.unit_cnt[u]) // 2])
+                  for u in np.nonzero(rows.unit_cnt > 0)[0]]
+        chosen = list(dict.fromkeys(chosen))[:n_sample]
+        have = set(chosen)
+        for t in np.linspace(0, cfg.T - 1, n_sample).astype(int):
+            if len(chosen) >= n_sample:
+                break
+            if int(t) not in have:
+                chosen.append(int(t))
+                have.add(int(t))
+        tokens = np.array(sorted(chosen), np.int64)
+        n_sample = len(tokens)
+        how = f"{n_sample} tokens (one from every active execution unit, the rest evenly spaced)"
         src = {"expert": L.experts, "united": united, "shared": L.shared}
-        cache = {}
-
-        def get(kind, i):
-            if (kind, i) not in cache:
-                cache[(kind, i)] = tuple(f32(a[i]) for a in src[kind])
-            return cache[(kind, i)]
-        for t in tokens:                                           # fetch weights outside the timed part
+        need = set(("shared", s) for s in range(cfg.n_shared))
+        for t in tokens:
             for j in range(cfg.K):
                 u = int(r.expert_unit[r.topk_idx[t, j]])
                 if u >= 0:
-                    get("expert", u) if u < cfg.m else get("united", u - cfg.m)
-        for s in range(cfg.n_shared):
-            get("shared", s)
-        cores = 1                                                   # one row per FFN call: no parallel loop
+                    need.add(("expert", u) if u < cfg.m else ("united", u - cfg.m))
+        t_fetch, t_ffn, out_rows = 0.0, 0.0, None
+        # the helper asks for each FFN once: time the fetches apart from the arithmetic
+        def get(kind, i):
+            nonlocal t_fetch
+            tf = time.perf_counter()
+            w = tuple(f32(a[i]) for a in src[kind])
+            t_fetch += time.perf_counter() - tf
+            return w
         t0 = time.perf_counter()
-        O.forward_tokens_lazy(x[tokens], r.topk_idx[tokens], r.topk_w[tokens], r.expert_unit, cfg.m, get,
-                              cfg.n_shared)
-        t_ffn = time.perf_counter() - t0
+        O.forward_tokens_lazy(x[tokens], r.topk_idx[tokens], r.topk_w[tokens], r.expert_unit, cfg.m, get, cfg.n_shared)
+        t_ffn = time.perf_counter() - t0 - t_fetch
+        log(f"  oracle: {len(need)} FFNs fetched from the GPU in {t_fetch:.2f} s (not counted)")
     per_token = t_route / cfg.T + t_ffn / n_sample
     log(f"  oracle: routing {t_route:.2f} s for {cfg.T} tokens, layer equation {t_ffn:.2f} s for {n_sample} tokens, "
         f"{cores} threads")
     return {"value": 1.0 / per_token, "unit": "tokens/s", "cores": cores, "kind": "oracle",
-            "sample": f"routing on all {cfg.T} tokens ({t_route:.2f} s) + layer equation on {n_sample} evenly spaced "
-                      f"tokens ({t_ffn:.2f} s), extrapolated linearly"}
+            "sample": f"routing on all {cfg.T} tokens ({t_route:.2f} s) + layer equation on {how} "
+                      f"({t_ffn:.2f} s), extrapolated linearly"}
 
 
 if __name__ == "__main__":
