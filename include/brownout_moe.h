@@ -121,13 +121,14 @@ moe_status moe_workspace_size(const moe_config *cfg, int32_t T_max, size_t *byte
 
 /*
  * One-time repack of the gate matrix (section "Architecture of BrownoutMoE": the
- * centroids e_i of the affinity s_{i,t} = x_t . e_i).  The gate runs on the bf16
- * matrix cores with every fp32 weight cut into three bf16 pieces (hi + mid + lo
- * carry its 24-bit significand, so x . e_i keeps fp32 accuracy).  With
- * cfg->gate_format == MOE_GATE_FP32 moe_route / moe_forward cut gate_w on every
- * call; a caller whose gate does not change between calls does it once here and
- * passes `packed` as gate_w with cfg->gate_format == MOE_GATE_PACKED.  Results are
- * bit-identical either way.
+ * centroids e_i of the affinity s_{i,t} = x_t . e_i).  With more than 16 experts the
+ * gate runs on the bf16 matrix cores with every fp32 weight cut into three bf16
+ * pieces (hi + mid + lo carry its 24-bit significand, so x . e_i keeps fp32
+ * accuracy).  With cfg->gate_format == MOE_GATE_FP32 moe_route / moe_forward cut
+ * gate_w on every call; a caller whose gate does not change between calls does it
+ * once here and passes `packed` as gate_w with cfg->gate_format ==
+ * MOE_GATE_PACKED.  Results are bit-identical either way.  (With at most 16
+ * experts the gate is plain fp64 arithmetic that reads either form as it is.)
  *   gate_w [m][d] fp32 (device)    packed: moe_gate_packed_size bytes (device)
  * Errors: NULL / misaligned pointers, packed_bytes too small (MOE_ERR_WORKSPACE).
  */
@@ -201,8 +202,8 @@ moe_status moe_route(const moe_config *cfg, const void *x, int32_t T, const void
  * The call allocates and frees nothing (profiling, moe_profile_enable, must be off:
  * it creates events).  A batch whose routing work space exceeds 8 MiB is rejected
  * with MOE_ERR_WORKSPACE before anything is launched; the need is about
- * T*(K+N_s)*12 + T*K*8 + T/64*U*8 bytes, plus 6*16*ceil(m/16)*d for an unpacked gate
- * (pack it with moe_pack_gate to save that).  All calls on one GPU share the array:
+ * T*(K+N_s)*12 + T*K*8 + T/64*U*8 bytes, plus 6*16*ceil(m/16)*d for an unpacked gate of
+ * more than 16 experts (pack it with moe_pack_gate to save that).  All calls on one GPU share the array:
  * two such calls whose work overlaps in time (different streams) race; calls on one
  * stream are safe, and nothing an earlier call left in the array is read.
  */

@@ -166,10 +166,12 @@ static void carve_route_pieces(const Dims& D, Workspace& W, size_t& o)
     W.token_rows = take((size_t)D.row_cap * 4);
     W.n_rows = take(4);
     W.near_tie = take((size_t)D.T);
-    W.gate_split = take(D.gate_format == MOE_GATE_PACKED ? 0 : (size_t)3 * D.m_pad * D.d * 2);
+    // the pieces of an fp32 gate matrix.  A packed gate of more than 16 experts brings them; with at most 16
+    // experts the gate is fp32 rows in either format, cut on the way only beyond kFewExpertsTokens tokens
+    const bool no_pieces = D.m_pad == 16 ? D.T <= kFewExpertsTokens : D.gate_format == MOE_GATE_PACKED;
+    W.gate_split = take(no_pieces ? 0 : (size_t)3 * D.m_pad * D.d * 2);
     W.seg_cnt = take((size_t)D.n_seg * D.U * 4);
     W.seg_off = take((size_t)D.n_seg * D.U * 4);
-    W.gate_hist = take((size_t)ceil_div(std::min(D.T, kSmallRouteTokens), 16) * D.m_pad * 4);
 }
 
 Workspace carve_workspace(const Dims& D)
@@ -407,8 +409,7 @@ moe_status moe_route(const moe_config* cfg, const void* x, int32_t T, const void
     none.n = 0; none.cap = 0;
     hipError_t e = launch_route(D, static_cast<const bf16_t*>(x), gate_w, gate_bias, threshold,
                                 use_full_brownout ? 1 : 0, R, at<bf16_t>(workspace, W.gate_split),
-                                at<int32_t>(workspace, W.seg_cnt), at<int32_t>(workspace, W.seg_off),
-                                at<int32_t>(workspace, W.gate_hist), none, s);
+                                at<int32_t>(workspace, W.seg_cnt), at<int32_t>(workspace, W.seg_off), none, s);
     if (e != hipSuccess) return hip_fail(e, "moe_route");
     return MOE_OK;
 }
@@ -435,8 +436,7 @@ moe_status moe_route_static(const moe_config* cfg, const void* x, int32_t T, con
     // everything the kernels read from the scratch they write first in the same call (counters are cleared by
     // the first kernel), so what an earlier call left there does not matter
     e = launch_route(D, static_cast<const bf16_t*>(x), gate_w, gate_bias, threshold, use_full_brownout ? 1 : 0, R,
-                     at<bf16_t>(sp, W.gate_split), at<int32_t>(sp, W.seg_cnt), at<int32_t>(sp, W.seg_off),
-                     at<int32_t>(sp, W.gate_hist), none, s);
+                     at<bf16_t>(sp, W.gate_split), at<int32_t>(sp, W.seg_cnt), at<int32_t>(sp, W.seg_off), none, s);
     if (e != hipSuccess) return hip_fail(e, "moe_route_static");
     return MOE_OK;
 }
@@ -500,7 +500,7 @@ moe_status moe_forward(const moe_config* cfg, const void* x, int32_t T, const vo
     if (!route) {
         e = launch_route(D, xb, gate_w, gate_bias, threshold, use_full_brownout ? 1 : 0, R,
                          at<bf16_t>(workspace, W.gate_split), at<int32_t>(workspace, W.seg_cnt),
-                         at<int32_t>(workspace, W.seg_off), at<int32_t>(workspace, W.gate_hist), jobs, s);
+                         at<int32_t>(workspace, W.seg_off), jobs, s);
         if (e != hipSuccess) return hip_fail(e, "moe_forward/route");
     }
     const bool built = route == nullptr;

@@ -18,6 +18,7 @@ constexpr int kMaxUnits = kMaxExperts + kMaxExperts + kMaxShared;  // U
 constexpr int kSegTokens = 64;    // tokens per routing segment (one wavefront)
 constexpr int kSmallSegs = 16;    // batches of at most this many segments are routed by ONE block
 constexpr int kSmallRouteTokens = kSmallSegs * kSegTokens;
+constexpr int kFewExpertsTokens = 2048;   // at most 16 experts and this many tokens: the fp64 gate (no matrix cores)
 constexpr int kMinTileRows = 32;  // smallest GEMM M tile
 constexpr int kTailBlocks = 256;  // largest grid of the persistent GEMM whose K-split tail has scratch (one block per CU)
 
@@ -66,7 +67,6 @@ struct Workspace {
         token_rows, n_rows, near_tie;                 // default homes of the moe_route_out fields
     size_t gate_split;                                // [3][m_pad][d] bf16
     size_t seg_cnt, seg_off;                          // [n_seg][U] int32
-    size_t gate_hist;                                 // [blocks of the gate][m_pad] int32 (small batches only)
     size_t route_total;                               // bytes of the pieces above (all that routing alone needs)
     size_t tiles0, tiles1;                            // two GEMM tile tables: int32[4] header + int4 entries
     size_t H;                                         // [h_rows][Fmax] bf16
@@ -101,7 +101,7 @@ struct TileJobs;
 // (jobs.n == 0: none).
 hipError_t launch_route(const Dims& D, const bf16_t* x, const void* gate, const float* gate_bias,
                         double threshold, int full_brownout, const RouteBufs& R, bf16_t* gate_split,
-                        int32_t* seg_cnt, int32_t* seg_off, int32_t* gate_hist, const TileJobs& jobs, hipStream_t s);
+                        int32_t* seg_cnt, int32_t* seg_off, const TileJobs& jobs, hipStream_t s);
 hipError_t launch_pack_gate(const float* gate_w, int m, int m_pad, int d, bf16_t* packed, hipStream_t s);
 
 // ---- FFN (ffn.hip) ----

@@ -61,8 +61,9 @@ __global__ void __launch_bounds__(256) prep_kernel(const float* __restrict__ gat
 struct GateArgs {
     const bf16_t* x; const unsigned short* split; const float* bias;
     int T, d, m, m_pad, K, score_fn, NG, KS, n_stage;
-    int32_t* topk_idx; float* topk_w; int32_t* expert_cnt; uint8_t* near_tie;
-    int32_t* block_hist;   // [blocks][m_pad]: per-block expert counts instead of atomics on expert_cnt (or null)
+    int32_t* topk_idx; float* topk_w; uint8_t* near_tie;
+    int32_t* expert_cnt;   // the launch's expert counts, cleared beforehand (atomics); null for small batches,
+                           // whose routing block counts the experts itself
 };
 
 // TopK(.,K) of one token by one wavefront: lane holds experts lane, lane+64, ...; K (+1 for the best
@@ -315,11 +316,94 @@ __global__ void __launch_bounds__(1024) gate_topk_kernel(GateArgs p)
     // TopK: one token per wavefront
     if (t0 + wave < p.T) topk_token(p, logit + wave * p.m_pad, t0 + wave, lane, hist);
     __syncthreads();
-    if (p.block_hist != nullptr) {
-        for (int i = tid; i < p.m_pad; i += 1024) p.block_hist[(size_t)blockIdx.x * p.m_pad + i] = hist[i];
-    } else {
+    if (p.expert_cnt != nullptr)
         for (int i = tid; i < p.m; i += 1024)
             if (hist[i] > 0) atomicAdd(&p.expert_cnt[i], hist[i]);
+}
+
+// ------------------------------------------------------------------------------------------------
+// gate for at most 16 experts and at most kFewExpertsTokens tokens: plain fp64 arithmetic, no matrix cores.
+// With so few experts and tokens what the gate needs is many blocks in flight (a CU pulls its share of x and
+// the whole gate matrix at the rate of the few loads it keeps in flight), not MFMA tiles padded from m to 16
+// columns: 15 us instead of 24 for 256 tokens of width 4096.  (Beyond a few thousand tokens the MFMA gate, which
+// reads the gate matrix once per 16 tokens, is faster again: 28 us against 44 at 4096 tokens.)  One block = TPB tokens, 256 threads; thread t multiplies the k range
+// 8t .. 8t+7 (+2048, ...) of the tokens' rows with every centroid, products and sums in double (a bf16 times an
+// fp32 value is exact there), the 256 partial sums of a (token, expert) pair are added in a fixed order through
+// LDS, and one wavefront per token takes TopK.  The centroids are read as fp32 rows (for at most 16 experts the
+// packed form of the gate is a copy of them).
+// ------------------------------------------------------------------------------------------------
+template <int M, int TPB>
+__global__ void __launch_bounds__(256) gate_small_kernel(GateArgs p, const float* __restrict__ gate_w)
+{
+    constexpr int NP = TPB * M;                           // (token, expert) pairs of the block
+    __shared__ double part[NP][33];
+    __shared__ float logit[TPB][16];
+    __shared__ int hist[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int t0 = blockIdx.x * TPB;
+    if (tid < 16) hist[tid] = 0;
+    double acc[TPB][M];
+#pragma unroll
+    for (int q = 0; q < TPB; ++q)
+#pragma unroll
+        for (int e = 0; e < M; ++e) acc[q][e] = 0.0;
+    for (int k = tid * 8; k < p.d; k += 2048) {
+        double xv[TPB][8];
+#pragma unroll
+        for (int q = 0; q < TPB; ++q) {
+            const int t = min(t0 + q, p.T - 1);
+            const uint4 raw = *reinterpret_cast<const uint4*>(p.x + (size_t)t * p.d + k);
+            const unsigned w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                xv[q][2 * c] = (double)__uint_as_float(w[c] << 16);
+                xv[q][2 * c + 1] = (double)__uint_as_float(w[c] & 0xFFFF0000u);
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < M; ++e) {
+            double wv[8];
+            if (e < p.m) {
+                {
+                    const float4 a = *reinterpret_cast<const float4*>(gate_w + (size_t)e * p.d + k);
+                    const float4 b = *reinterpret_cast<const float4*>(gate_w + (size_t)e * p.d + k + 4);
+                    wv[0] = a.x; wv[1] = a.y; wv[2] = a.z; wv[3] = a.w;
+                    wv[4] = b.x; wv[5] = b.y; wv[6] = b.z; wv[7] = b.w;
+                }
+#pragma unroll
+                for (int q = 0; q < TPB; ++q)
+#pragma unroll
+                    for (int c = 0; c < 8; ++c) acc[q][e] = fma(xv[q][c], wv[c], acc[q][e]);
+            }
+        }
+    }
+    // the 256 partial sums of a pair: eight neighbouring lanes first (three exchange steps), then the 32 group
+    // sums in order by one thread
+#pragma unroll
+    for (int q = 0; q < TPB; ++q)
+#pragma unroll
+        for (int e = 0; e < M; ++e) {
+            double v = acc[q][e];
+            v += __shfl_xor(v, 1);
+            v += __shfl_xor(v, 2);
+            v += __shfl_xor(v, 4);
+            if ((lane & 7) == 0) part[q * M + e][tid >> 3] = v;
+        }
+    __syncthreads();
+    if (tid < NP) {
+        const int q = tid / M, e = tid - q * M;
+        if (e < p.m) {
+            double s = 0.0;
+            for (int i = 0; i < 32; ++i) s += part[tid][i];
+            if (p.bias != nullptr) s += (double)p.bias[e];
+            logit[q][e] = (float)s;
+        }
+    }
+    __syncthreads();
+    if (wave < TPB && t0 + wave < p.T) topk_token(p, logit[wave], t0 + wave, lane, hist);
+    if (p.expert_cnt != nullptr) {                        // large batches: the launch's counts (cleared beforehand)
+        __syncthreads();
+        if (tid < p.m && hist[tid] > 0) atomicAdd(&p.expert_cnt[tid], hist[tid]);
     }
 }
 
@@ -552,8 +636,7 @@ struct RowArgs {
     int32_t* seg_cnt; int32_t* seg_off;
     int32_t* unit_cnt; int32_t* unit_off; int32_t* n_rows;
     int32_t* row_token; float* row_weight; int32_t* token_rows;
-    const int32_t* block_hist; int n_hist_blocks, m_pad;   // small batches: per-block expert counts of the gate
-    int32_t* expert_cnt_out;                               // ... and where their sum goes
+    int32_t* expert_cnt_out;                               // small batches: the routing block counts the experts itself
     TileJobs jobs;                                         // GEMM tile tables to build (jobs.n == 0: none)
 };
 
@@ -723,15 +806,14 @@ __global__ void __launch_bounds__(1024) route_small_kernel(RowArgs p)
     unsigned long long* bm = reinterpret_cast<unsigned long long*>(rsm);                      // [16][U]
     int* segoff = reinterpret_cast<int*>(rsm + (size_t)kSmallSegs * p.U * 8);                  // [16][U]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid < p.m) {
-        // cnt_i: the sum of the gate blocks' counts (in block order; integers, so any order gives the same)
-        int c = 0;
-        for (int b = 0; b < p.n_hist_blocks; ++b) c += p.block_hist[(size_t)b * p.m_pad + tid];
-        cnt_s[tid] = c;
-        p.expert_cnt_out[tid] = c;
-    }
+    // cnt_i (the input of Algorithm 1) straight from the TopK lists: at most 1024 tokens, one thread each
+    if (tid < p.m) cnt_s[tid] = 0;
     for (int i = tid; i < kSmallSegs * p.U; i += 1024) bm[i] = 0ull;
     __syncthreads();
+    if (tid < p.T)
+        for (int j = 0; j < p.K; ++j) atomicAdd(&cnt_s[p.topk_idx[(size_t)tid * p.K + j]], 1);
+    __syncthreads();
+    if (tid < p.m) p.expert_cnt_out[tid] = cnt_s[tid];
     brownout_decide(cnt_s, s2_s, unit_s, p.m, p.way, p.threshold, p.full, tid, true, p.expert_unit, p.expert_in_s1);
     const int t = wave * kSegTokens + lane;
     mark_units(p, unit_s, bm + (size_t)wave * p.U, t, lane);
@@ -793,6 +875,8 @@ hipError_t init_route_kernels()
 
 hipError_t launch_pack_gate(const float* gate_w, int m, int m_pad, int d, bf16_t* packed, hipStream_t s)
 {
+    if (m_pad == 16)     // at most 16 experts: the fp64 gate reads fp32 rows, the packed form is a copy of them
+        return hipMemcpyAsync(packed, gate_w, (size_t)m * d * 4, hipMemcpyDeviceToDevice, s);
     const size_t n = (size_t)m_pad * d;
     const int blocks = (int)std::min<size_t>((n + 255) / 256, 2048);
     prep_kernel<<<blocks, 256, 0, s>>>(gate_w, m, m_pad, d, reinterpret_cast<unsigned short*>(packed), nullptr);
@@ -801,39 +885,48 @@ hipError_t launch_pack_gate(const float* gate_w, int m, int m_pad, int d, bf16_t
 
 hipError_t launch_route(const Dims& D, const bf16_t* x, const void* gate, const float* gate_bias,
                         double threshold, int full_brownout, const RouteBufs& R, bf16_t* gate_split,
-                        int32_t* seg_cnt, int32_t* seg_off, int32_t* gate_hist, const TileJobs& jobs, hipStream_t s)
+                        int32_t* seg_cnt, int32_t* seg_off, const TileJobs& jobs, hipStream_t s)
 {
     hipError_t e = ensure_device_init(nullptr);
     if (e != hipSuccess) return e;
-    const bool small = D.n_seg <= kSmallSegs;            // one block routes the whole batch
+    const bool small = D.n_seg <= kSmallSegs;            // one block routes the whole batch (and counts the experts)
     const bool packed = D.gate_format == MOE_GATE_PACKED;
-    // Small batches: the gate blocks leave their expert counts side by side and the routing block adds them
-    // up, so nothing has to be cleared first; with a packed gate there is then no preparation launch at all.
-    if (!packed || !small) {
+    // At most 16 experts: the gate matrix is fp32 rows in either format, and up to kFewExpertsTokens tokens the
+    // plain fp64 gate reads them as they are (larger batches: cut here on every call, 6 us, then the MFMA gate).
+    const bool few_fmt = D.m_pad == 16;
+    const bool few = few_fmt && D.T <= kFewExpertsTokens;
+    // Preparation: cut an fp32 gate matrix into its pieces (only the MFMA gates need them) and clear the expert
+    // counters (only large batches use them).  A small batch with a packed gate or few experts needs neither.
+    const bool split = !few && (!packed || few_fmt);
+    if (split || !small) {
         ProfScope ps(MOE_STAGE_PREP, s);
-        const size_t n = packed ? (size_t)D.m : (size_t)D.m_pad * D.d;
+        const size_t n = split ? (size_t)D.m_pad * D.d : (size_t)D.m;
         const int blocks = (int)std::min<size_t>((n + 255) / 256, 2048);
-        prep_kernel<<<blocks, 256, 0, s>>>(packed ? nullptr : static_cast<const float*>(gate), D.m, D.m_pad, D.d,
-                                           packed ? nullptr : reinterpret_cast<unsigned short*>(gate_split),
+        prep_kernel<<<blocks, 256, 0, s>>>(split ? static_cast<const float*>(gate) : nullptr, D.m, D.m_pad, D.d,
+                                           split ? reinterpret_cast<unsigned short*>(gate_split) : nullptr,
                                            small ? nullptr : R.expert_cnt);
     }
     {
         ProfScope ps(MOE_STAGE_GATE, s);
         GateArgs g;
         g.x = x;
-        g.split = packed ? static_cast<const unsigned short*>(gate) : reinterpret_cast<const unsigned short*>(gate_split);
+        g.split = split ? reinterpret_cast<const unsigned short*>(gate_split) : static_cast<const unsigned short*>(gate);
         g.bias = gate_bias;
         g.T = D.T; g.d = D.d; g.m = D.m; g.m_pad = D.m_pad; g.K = D.K; g.score_fn = D.score_fn; g.n_stage = 3;
         const int n_tiles = D.m_pad / 16;
         g.NG = n_tiles < 4 ? n_tiles : 4;
         g.KS = std::max(1, std::min(16 / g.NG, 256 / D.m_pad));
         const int ntw = ceil_div(n_tiles, g.NG);
-        g.topk_idx = R.topk_idx; g.topk_w = R.topk_w; g.expert_cnt = R.expert_cnt; g.near_tie = R.near_tie;
-        g.block_hist = small ? gate_hist : nullptr;
+        g.topk_idx = R.topk_idx; g.topk_w = R.topk_w; g.near_tie = R.near_tie;
+        g.expert_cnt = small ? nullptr : R.expert_cnt;
         // many experts and enough tokens to fill the CUs with wider token tiles: LDS-staged variant
         const int half_tiles = ceil_div(n_tiles, 2);
         const int tgw = D.T >= 64 * 192 ? 4 : (D.T >= 32 * 192 ? 2 : 0);
-        if (n_tiles >= 4 && tgw != 0) {
+        if (few) {
+            const float* gw = static_cast<const float*>(gate);      // fp32 rows in either gate format
+            if (D.m <= 8) gate_small_kernel<8, 1><<<D.T, 256, 0, s>>>(g, gw);
+            else gate_small_kernel<16, 1><<<D.T, 256, 0, s>>>(g, gw);
+        } else if (n_tiles >= 4 && tgw != 0) {
             const int rows = 3 * D.m_pad + 16 * tgw;
             const bool wide = D.m_pad <= 128 && 3 * rows * 128 <= kGateLds - 1024;    // 64-wide k stages fit
             const int stage = rows * (wide ? 128 : 64);
@@ -869,7 +962,7 @@ hipError_t launch_route(const Dims& D, const bf16_t* x, const void* gate, const 
     p.full = full_brownout; p.threshold = threshold;
     p.seg_cnt = seg_cnt; p.seg_off = seg_off; p.unit_cnt = R.unit_cnt; p.unit_off = R.unit_off; p.n_rows = R.n_rows;
     p.row_token = R.row_token; p.row_weight = R.row_weight; p.token_rows = R.token_rows;
-    p.block_hist = gate_hist; p.n_hist_blocks = ceil_div(D.T, 16); p.m_pad = D.m_pad; p.expert_cnt_out = R.expert_cnt;
+    p.expert_cnt_out = R.expert_cnt;
     p.jobs = jobs;
     if (small) {
         ProfScope ps(MOE_STAGE_COUNT, s);

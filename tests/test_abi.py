@@ -107,8 +107,12 @@ def test_packed_gate_size_and_validation():
     with pytest.raises(P.MoeError) as ei:
         P.workspace_size(bad, 64)
     assert ei.value.status == -1
-    # a packed gate needs no room for the pieces in the workspace
-    assert P.workspace_size(B.with_packed_gate(cfg), 64) < P.workspace_size(cfg, 64)
+    # a packed gate needs no room for the pieces in the workspace (nor does an fp32 gate of at most 16 experts,
+    # which is read as it is)
+    cfg32 = P.make_config(256, 512, 32, 2, 8)
+    assert P.workspace_size(B.with_packed_gate(cfg32), 64) < P.workspace_size(cfg32, 64)
+    assert P.workspace_size(B.with_packed_gate(cfg), 64) == P.workspace_size(cfg, 64)
+    assert P.workspace_size(B.with_packed_gate(cfg), 4096) == P.workspace_size(cfg, 4096)
 
 
 def test_activations_beyond_32_bit_offsets_are_refused():
