@@ -1040,23 +1040,52 @@ __global__ void __launch_bounds__(256) combine_kernel(const bf16_t* __restrict__
             a[2 * e + 1] += (float)h[1];
         }
     };
-    // one row of the FFN output: its K-split planes summed in order, then times the row's weight
-    auto add_ffn_row = [&](int r) {
-        float part[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) part[e] = 0.0f;
-        for (int q = 0; q < ksplit; ++q) add_y_row(Y + q * plane + (long)r * d, part);
-        const float w = row_weight[r];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] += w * part[e];
-    };
+    // The token's rows in the order of the sum (shared experts first, then the TopK entries), eight at a time:
+    // their indices and weights first, then all their loads, then the additions in order, so that a thread keeps
+    // several 16-byte loads in flight instead of one.  A row's K-split planes are summed first, then the sum is
+    // multiplied by the row's weight.
     if (add_residual) add_row(x + (long)t * d, acc);
     const int slots = K + Ns;
     const int32_t* tr = token_rows + (long)t * slots;
-    for (int s = 0; s < Ns; ++s) add_ffn_row(tr[K + s]);
-    for (int j = 0; j < K; ++j) {
-        const int r = tr[j];
-        if (r >= 0) add_ffn_row(r);
+    constexpr int CB = 8;                                 // rows in flight per thread
+    for (int s0 = 0; s0 < slots; s0 += CB) {
+        int r[CB];
+        float w[CB];
+#pragma unroll
+        for (int u = 0; u < CB; ++u) {
+            const int sp = s0 + u;
+            r[u] = sp < slots ? tr[sp < Ns ? K + sp : sp - Ns] : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < CB; ++u) w[u] = r[u] >= 0 ? row_weight[r[u]] : 0.0f;
+        if (ksplit == 1) {
+            uint4 q[CB];
+#pragma unroll
+            for (int u = 0; u < CB; ++u)
+                q[u] = r[u] >= 0 ? *reinterpret_cast<const uint4*>(Y + (long)r[u] * d + c8) : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+            for (int u = 0; u < CB; ++u) {
+                if (r[u] < 0) continue;
+                const unsigned int v[4] = {q[u].x, q[u].y, q[u].z, q[u].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const f16x2 h = __builtin_bit_cast(f16x2, v[e]);
+                    acc[2 * e] += w[u] * (float)h[0];
+                    acc[2 * e + 1] += w[u] * (float)h[1];
+                }
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < CB; ++u) {
+                if (r[u] < 0) continue;
+                float part[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) part[e] = 0.0f;
+                for (int pz = 0; pz < ksplit; ++pz) add_y_row(Y + pz * plane + (long)r[u] * d, part);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[e] += w[u] * part[e];
+            }
+        }
     }
     uint4 o;
     o.x = pack_bf16(acc[0], acc[1]);
