@@ -225,7 +225,7 @@ def main():
                   "tokens_per_s": d0["tokens_per_s"], "route_ms": d0["route_ms"],
                   "layer_roofline_frac": d0["layer_frac"], "bytes_min": d0["bytes_min"],
                   "bytes_two_gemm": d0["bytes_two_gemm"], "roofline": d0["roofline"],
-                  "full_brownout_fraction_1": {"ms_per_step": d1["ms_per_step"], "tokens_per_s": d1["tokens_per_s"],
+                  "brownout_fraction_1": {"ms_per_step": d1["ms_per_step"], "tokens_per_s": d1["tokens_per_s"],
                                                "bytes_min": d1["bytes_min"], "layer_roofline_frac": d1["layer_frac"],
                                                "gemm1_gbs": d1["roofline"]["achieved"]}}
     line = {
