@@ -17,7 +17,6 @@ constexpr int kMaxShared = 8;     // N_s
 constexpr int kMaxUnits = kMaxExperts + kMaxExperts + kMaxShared;  // U
 constexpr int kSegTokens = 64;    // tokens per routing segment (one wavefront)
 constexpr int kSmallSegs = 16;    // batches of at most this many segments are routed by ONE block
-constexpr int kSmallRouteTokens = kSmallSegs * kSegTokens;
 constexpr int kFewExpertsTokens = 2048;   // at most 16 experts and this many tokens: the fp64 gate (no matrix cores)
 constexpr int kMinTileRows = 32;  // smallest GEMM M tile
 constexpr int kTailBlocks = 256;  // largest grid of the persistent GEMM whose K-split tail has scratch (one block per CU)
