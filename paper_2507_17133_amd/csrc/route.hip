@@ -1,11 +1,16 @@
 // Routing kernels of the BrownoutMoE layer for gfx950:
-//   prep     clear the expert counters, split the fp32 gate weights into three bf16 pieces
-//   gate     affinities s = x.e_i on MFMA (bf16 x 3-piece weights, fp64 running sums), TopK by
-//            wavefront shuffles, weights g, expert histogram        (Architecture of BrownoutMoE)
+//   prep     clear the expert counters (large batches), split fp32 gate weights into three bf16 pieces
+//            (also the one-time repack behind moe_pack_gate)
+//   gate     affinities s = x.e_i on MFMA (bf16 x 3-piece weights, fp64 running sums) or, for at most 16
+//            experts and small batches, in plain fp64; TopK by wavefront shuffles, weights g, expert
+//            histogram                                               (Architecture of BrownoutMoE)
 //   count    Algorithm 1's S1/S2 split and unit map (every block, from the counts) and the rows
 //            each 64-token segment gives each unit                   (Brownout Approach, Algorithm 1)
 //   scan     offsets of segments inside units, unit totals (unit offsets: scanned by the scatter blocks)
-//   scatter  row lists: row_token, row_weight, token_rows (stable: ascending token inside a unit)
+//   scatter  row lists: row_token, row_weight, token_rows (stable: ascending token inside a unit); its first
+//            block also writes the GEMM tile table
+//   small    at most 1024 tokens: expert counts, Algorithm 1, both scans, the scatter and the tile table
+//            in ONE block
 // No floating-point atomics anywhere; integer atomics only where the result does not depend on order.
 #include "internal.h"
 #include "tiles.h"
