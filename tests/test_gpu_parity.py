@@ -68,6 +68,12 @@ SMALL = {
     # ... also when the shared experts have fewer k tiles than there are planes (empty slices: zeros)
     "shared_narrower_than_planes": (WL.LayerConfig("shared_narrower_than_planes", T=600, d=128, F=2048, m=16, K=2,
                                                    way=4, n_shared=1, F_s=64), [1.0]),
+    # at most 16 experts: the plain fp64 gate up to 2048 tokens, the MFMA gate (pieces cut from the fp32 rows on the
+    # way, whichever format the caller passes) from 2049 on
+    "few_experts_2048_tokens": (WL.LayerConfig("few_experts_2048_tokens", T=2048, d=64, F=64, m=16, K=3, way=4,
+                                               zipf_s=1.0), [0.5]),
+    "few_experts_2049_tokens": (WL.LayerConfig("few_experts_2049_tokens", T=2049, d=64, F=64, m=16, K=3, way=4,
+                                               zipf_s=1.0), [0.5]),
     # the largest K and number of shared experts the library accepts
     "max_topk_max_shared": (WL.LayerConfig("max_topk_max_shared", T=48, d=64, F=64, m=64, K=32, way=8, n_shared=8,
                                            F_s=64), [1.0, 0.5]),
