@@ -221,6 +221,7 @@ __device__ __forceinline__ void store_tile(const GemmArgs& p, const Tile& t, con
 // branch-free block the scheduler can interleave freely (a lone wave per SIMD has nothing else to hide
 // the latency of exp and rcp behind), then stored row by row under the row mask.  N is a multiple of 64,
 // so a 64-column group of a wave tile is either entirely inside the matrix or entirely outside.
+// (Used by the column-half tiles of the tail; whole tiles take store_tile16_lines below.)
 template <int FM, int FN, int TM, int TN, bool SWIGLU>
 __device__ __forceinline__ void store_tile16(const GemmArgs& p, const Tile& t, const f32x4 (&acc)[FM][FN], int wm,
                                              int wn, int lane)
@@ -257,6 +258,90 @@ __device__ __forceinline__ void store_tile16(const GemmArgs& p, const Tile& t, c
                 const int cbase = SWIGLU ? t.n0 + (wn * (TN / 32) + g) * 16 : t.n0 + wn * TN + g * 16;
                 if (cbase < p.N) *reinterpret_cast<uint2*>(orow + cbase + 4 * (lane >> 4)) = res[ii][g];
             }
+        }
+    }
+}
+
+// The same tile written in whole 128-byte lines.  In the accumulator layout neighbouring lanes hold different
+// rows, so a store instruction of store_tile16 reaches memory as 64 separate 8-byte writes; short K makes that
+// the largest cost of a GEMM2 tile.  Here each group of 16 rows x 64 output columns goes through 2 KiB of LDS
+// private to the wave (`scratch`: four 1 KiB pieces 4 KiB apart, free while the epilogue runs: the wave's own
+// load targets in the third B buffer that the first loads of the next tile do not use) and comes back as
+// rows: 8 lanes x 16 bytes per row, 8 rows per store instruction.  8-byte slot s of row r lives at slot
+// s ^ 2(r/2): both the 8-byte writes (16 lanes, one per row) and the 16-byte reads (16 lanes, two rows) are
+// free of bank conflicts.  LDS operations of a wave execute in order, so no barrier is needed.  The LDS
+// accesses are written as instructions: left to the compiler they are preceded by a wait for every direct
+// global->LDS load in flight (it cannot tell their targets from this scratch), i.e. for the next tile's first
+// loads, which were issued a moment ago to land behind this epilogue.
+template <int FM, int FN, int TM, int TN, bool SWIGLU>
+__device__ __forceinline__ void store_tile16_lines(const GemmArgs& p, const Tile& t, const f32x4 (&acc)[FM][FN], int wm,
+                                                   int wn, int lane, char* scratch)
+{
+    unsigned short* out = reinterpret_cast<unsigned short*>(p.out) + (size_t)t.kslice * p.plane;
+    constexpr int NG = SWIGLU ? FN / 2 : FN;             // 16-column groups of output per wave
+    static_assert(NG % 4 == 0, "units of 64 output columns");
+    constexpr int NU = NG / 4;                           // units per group of 16 rows
+    constexpr int NUT = FM * NU;                         // units of the wave tile
+    const unsigned base = (unsigned)(unsigned long)((__attribute__((address_space(3))) char*)scratch);
+    const int r = lane & 15, c = lane >> 4;
+    const int x = (r >> 1) << 1;
+    unsigned w_addr[4];
+#pragma unroll
+    for (int gl = 0; gl < 4; ++gl)
+        w_addr[gl] = base + (r >> 3) * 4096 + (r & 7) * 128 + ((c ^ (x & 3)) << 3) + ((gl * 32) ^ ((x & 12) << 3));
+    const int k = lane & 7, rr = lane >> 3;
+    unsigned r_addr[2];
+#pragma unroll
+    for (int rd = 0; rd < 2; ++rd)
+        r_addr[rd] = base + rd * 4096 + rr * 128 + (((2 * k) ^ (((rd * 8 + rr) >> 1) << 1)) << 3);
+    const int col0 = (SWIGLU ? t.n0 + wn * (TN / 2) : t.n0 + wn * TN) + k * 8;
+    // unit u = 16 rows x 64 output columns; units alternate between the two halves of the scratch, and the
+    // next unit is converted and written while the reads of the current one are in flight
+    auto convert_write = [&](int u) {
+        const int i = u / NU, h = u % NU;
+#pragma unroll
+        for (int gl = 0; gl < 4; ++gl) {
+            const int g = h * 4 + gl;
+            typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+            u32x2 v;
+            if (SWIGLU) {
+                float hh[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) hh[e] = swiglu(acc[i][2 * g][e], acc[i][2 * g + 1][e]);
+                v = u32x2{pack_bf16(hh[0], hh[1]), pack_bf16(hh[2], hh[3])};
+            } else {
+                v = u32x2{pack_f16(acc[i][g][0], acc[i][g][1]), pack_f16(acc[i][g][2], acc[i][g][3])};
+            }
+            if ((u & 1) == 0) asm volatile("ds_write_b64 %0, %1" ::"v"(w_addr[gl]), "v"(v) : "memory");
+            else asm volatile("ds_write_b64 %0, %1 offset:8192" ::"v"(w_addr[gl]), "v"(v) : "memory");
+        }
+    };
+    convert_write(0);
+#pragma unroll
+    for (int u = 0; u < NUT; ++u) {
+        u32x4 l0, l1;
+        if ((u & 1) == 0) {
+            asm volatile("ds_read_b128 %0, %1" : "=v"(l0) : "v"(r_addr[0]) : "memory");
+            asm volatile("ds_read_b128 %0, %1" : "=v"(l1) : "v"(r_addr[1]) : "memory");
+        } else {
+            asm volatile("ds_read_b128 %0, %1 offset:8192" : "=v"(l0) : "v"(r_addr[0]) : "memory");
+            asm volatile("ds_read_b128 %0, %1 offset:8192" : "=v"(l1) : "v"(r_addr[1]) : "memory");
+        }
+        if (u + 1 < NUT) {
+            convert_write(u + 1);
+            // LDS operations complete in order: all but the four writes just issued are done
+            asm volatile("s_waitcnt lgkmcnt(4)" : "+v"(l0), "+v"(l1)::"memory");
+        } else {
+            asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(l0), "+v"(l1)::"memory");
+        }
+        const int i = u / NU, h = u % NU;
+        const int col = col0 + h * 64;
+        const u32x4 line[2] = {l0, l1};
+#pragma unroll
+        for (int rd = 0; rd < 2; ++rd) {
+            const int rl = wm * TM + i * 16 + rd * 8 + rr;
+            if (rl < t.nrows && col < p.N)
+                *reinterpret_cast<u32x4*>(out + (long)(t.row0 + rl) * p.ldo + col) = line[rd];
         }
     }
 }
@@ -980,8 +1065,11 @@ __device__ __forceinline__ void w4_block(const GemmArgs& p, const int block, con
             int lane_e;
             asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(lane_e));
             const int wn_e = MODE == 2 ? q0 / 2 + (wave_s & 1) : (wave_s & 1);
-            if (MODE == 1)
+            if constexpr (MODE == 1)
                 store_partial16<FM, FN, TM, TN>(p.partial + (size_t)tcur.part * 65536, acc, wave_s >> 1, wn_e, lane_e);
+            else if constexpr (MODE == 0)
+                store_tile16_lines<FM, FN, TM, TN, SWIGLU>(p, tcur, acc, wave_s >> 1, wn_e, lane_e,
+                                                           smem + B_BASE + 2 * BBUF + (wave_s + 2 * NW) * 1024);
             else
                 store_tile16<FM, FN, TM, TN, SWIGLU>(p, tcur, acc, wave_s >> 1, wn_e, lane_e);
         }
