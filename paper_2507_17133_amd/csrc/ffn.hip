@@ -216,6 +216,61 @@ __device__ __forceinline__ void store_tile(const GemmArgs& p, const Tile& t, con
     }
 }
 
+// The same tile written as whole row segments.  In the accumulator layout neighbouring lanes hold different
+// rows, so a store instruction of store_tile reaches memory as 64 separate 8-byte writes.  Here the wave tile
+// (32 FM rows x 64 tile columns: 64 output columns of GEMM2 = one 128-byte line per row, 32 of GEMM1 = 64
+// bytes) goes through 4 KiB (2 KiB) per 32 rows of LDS private to the wave and comes back row-contiguous,
+// 16 bytes per lane.  `scratch`: 8 KiB of the stage buffers, which are free once every wave has left the k
+// loop (the caller's barrier).  8-byte slot s of row r lives at slot s ^ 2((r/2)&7) (rows of 64 bytes:
+// s ^ 2((r/4)&3)): writes and reads are free of bank conflicts.  fp32 output keeps the plain path.
+template <int FM, int FN, int TM, int TN, bool SWIGLU>
+__device__ __forceinline__ void store_tile_lines(const GemmArgs& p, const Tile& t, const f32x16 (&acc)[FM][FN], int wm,
+                                                 int wn, int lane, char* scratch)
+{
+    static_assert(FN == 2 && FM <= 2, "wave tile of 64 tile columns, one scratch half per 32 rows");
+    if (p.out32) { store_tile<FM, FN, TM, TN, SWIGLU>(p, t, acc, wm, wn, lane); return; }
+    unsigned short* out = reinterpret_cast<unsigned short*>(p.out) + (size_t)t.kslice * p.plane;
+    const int r = lane & 31, hb = lane >> 5;
+    constexpr int ROWB = SWIGLU ? 64 : 128;                     // bytes of a row in the scratch
+    const int fx = SWIGLU ? ((r >> 2) & 3) << 1 : ((r >> 1) & 7) << 1;
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+        char* sc = scratch + i * 4096 + r * ROWB;
+        if (SWIGLU) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float h[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) h[e] = swiglu(acc[i][0][4 * q + e], acc[i][1][4 * q + e]);
+                *reinterpret_cast<uint2*>(sc + (((q * 2 + hb) ^ fx) << 3)) =
+                    make_uint2(pack_bf16(h[0], h[1]), pack_bf16(h[2], h[3]));
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    *reinterpret_cast<uint2*>(sc + (((j * 8 + q * 2 + hb) ^ fx) << 3)) =
+                        make_uint2(pack_f16(acc[i][j][4 * q], acc[i][j][4 * q + 1]),
+                                   pack_f16(acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]));
+        }
+    }
+    constexpr int LPR = ROWB / 16;                              // lanes per row on the way out: 8 or 4
+    constexpr int RPI = 64 / LPR;                               // rows per store instruction: 8 or 16
+    const int k = lane % LPR, rr = lane / LPR;
+    const int col = (SWIGLU ? t.n0 + wn * (TN / 2) : t.n0 + wn * TN) + k * 8;
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int rd = 0; rd < 32 / RPI; ++rd) {
+            const int row = rd * RPI + rr;
+            const int gx = SWIGLU ? ((row >> 2) & 3) << 1 : ((row >> 1) & 7) << 1;
+            const uint4 v = *reinterpret_cast<const uint4*>(scratch + i * 4096 + row * ROWB + (((2 * k) ^ gx) << 3));
+            const int rl = wm * TM + i * 32 + row;
+            if (rl < t.nrows && col < p.N) *reinterpret_cast<uint4*>(out + (long)(t.row0 + rl) * p.ldo + col) = v;
+        }
+}
+
 // Epilogue for 16x16 MFMA tiles (same transposed product): a lane holds, for output row lane&15, the four
 // consecutive columns 4*(lane>>4) + 0..3 of each 16x16 tile.  All values are converted first, as one
 // branch-free block the scheduler can interleave freely (a lone wave per SIMD has nothing else to hide
@@ -448,7 +503,8 @@ __global__ void __launch_bounds__(WM * WN * 64) ffn_gemm_kernel(GemmArgs p)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[j], af[i], acc[i][j], 0, 0, 0);
         }
     }
-    store_tile<FM, FN, TM, TN, SWIGLU>(p, t, acc, wm, wn, lane);
+    lds_barrier();                                        // every wave has left the stage buffers
+    store_tile_lines<FM, FN, TM, TN, SWIGLU>(p, t, acc, wm, wn, lane, smem + wave * 8192);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -597,7 +653,8 @@ __global__ void __launch_bounds__(512) ffn_gemm_pp_kernel(GemmArgs p)
         lds_barrier();
         main_loop(std::integral_constant<int, 1>{});
     }
-    store_tile<FM, FN, TM, TN, SWIGLU>(p, t, acc, wm, wn, lane);
+    lds_barrier();                                        // every wave has left the stage buffers
+    store_tile_lines<FM, FN, TM, TN, SWIGLU>(p, t, acc, wm, wn, lane, smem + wave * 8192);
 }
 
 // Tells the compiler that a pointer is the same in every lane (keeps it in scalar registers).
