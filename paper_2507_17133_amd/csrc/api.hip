@@ -23,7 +23,7 @@ constexpr int kMaxDevices = 64;
 
 static Tuning read_tuning()
 {
-    Tuning t{0, 4, 0};
+    Tuning t{0, 0, 0};
     if (const char* e = std::getenv("BROWNOUT_MOE_BM")) {
         const int v = std::atoi(e);
         if (v == 32 || v == 64 || v == 128 || v == 256) t.force_bm = v;

@@ -1349,7 +1349,7 @@ hipError_t launch_ffn(const Dims& D, int u_lo, int u_hi, int Fdim, const TilePla
     g1.m = D.m; g1.G = D.G; g1.N = Fdim; g1.K = D.d;
     g1.out = H; g1.ldo = D.Fmax;
     g1.n_ntiles = 0;                            // set by the launcher from its tile width
-    g1.group_m = tuning().group_m;
+    g1.group_m = tuning().group_m ? tuning().group_m : (plan.bm == 256 ? 8 : 4);
     g1.ksplit = 1; g1.plane = 0;
     g1.out32 = nullptr; g1.partial = partial; g1.partial_cap = D.tail_blocks;
     g1.table = table;
@@ -1365,7 +1365,7 @@ hipError_t launch_ffn(const Dims& D, int u_lo, int u_hi, int Fdim, const TilePla
     g2.m = D.m; g2.G = D.G; g2.N = D.d; g2.K = Fdim;
     g2.out = Y; g2.ldo = D.d;
     g2.n_ntiles = 0;
-    g2.group_m = tuning().group_m;
+    g2.group_m = g1.group_m;
     g2.ksplit = D.ksplit; g2.plane = D.y_plane;
     g2.out32 = nullptr; g2.partial = partial; g2.partial_cap = D.tail_blocks;
     g2.table = table;

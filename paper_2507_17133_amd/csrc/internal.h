@@ -27,7 +27,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 // Measurement switches, read from the environment ONCE (when the library is loaded); all unset in normal use.
 struct Tuning {
     int force_bm;      // BROWNOUT_MOE_BM = 32/64/128/256: one tile height for every unit (0: not forced)
-    int group_m;       // BROWNOUT_MOE_GM: M tiles per L2 super-tile of the GEMMs (default 4)
+    int group_m;       // BROWNOUT_MOE_GM: M tiles per L2 super-tile of the GEMMs (0: 8 for 256-row tiles, else 4)
     int force_ksplit;  // BROWNOUT_MOE_KSPLIT = 1/2/4: K planes of GEMM2 with small tiles (0: not forced)
 };
 const Tuning& tuning();

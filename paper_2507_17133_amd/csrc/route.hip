@@ -87,6 +87,13 @@ __device__ __forceinline__ void better(float& bv, int& bi, float ov, int oi)
     if (take) { bv = ov; bi = oi; }
 }
 
+// the same when both ids are real
+__device__ __forceinline__ void better_of_two(float& bv, int& bi, float ov, int oi)
+{
+    const bool take = ov > bv || (ov == bv && oi < bi);
+    if (take) { bv = ov; bi = oi; }
+}
+
 __device__ __forceinline__ void topk_token(const GateArgs& p, const float* logit_row, int t, int lane, int* hist)
 {
     const int K = p.K;
@@ -150,37 +157,42 @@ __device__ __forceinline__ void topk_token(const GateArgs& p, const float* logit
 }
 
 // The same for four tokens at a time: token `row` = lane >> 4 of the four is handled by the 16 lanes of its
-// row, lane r of the row holding experts r, r+16, ...; every reduction stays inside the row (rotations), so
-// the four selections run side by side.  Needs K + 1 <= 16 (lane j of the row keeps the j-th winner).
+// row, lane r of the row holding experts r, r+16, ... (NC of them: NC >= m_pad / 16); every reduction stays
+// inside the row (rotations), so the four selections run side by side.  A lane's experts that do not exist or
+// have been picked hold -infinity (logits are finite, and a row always has an expert left to pick), so a round
+// is a branch-free maximum over NC registers (first of equal values: the lower id) and four rotations.
+// Needs K + 1 <= 16 (lane j of the row keeps the j-th winner).
 // tl: this row's token inside the block's logit array, t: its global index, valid: whether it exists.
+template <int NC>
 __device__ __forceinline__ void topk_rows(const GateArgs& p, const float* logit, int tl, int t, bool valid, int lane, int* hist)
 {
     const int K = p.K, r = lane & 15;
     const int n_pick = K < p.m ? K + 1 : K;
     const float* logit_row = logit + tl * p.m_pad;
-    float v[16];
-    unsigned taken = 0;
+    const float none = -__builtin_inff();
+    float v[NC];
 #pragma unroll
-    for (int c = 0; c < 16; ++c) {
+    for (int c = 0; c < NC; ++c) {
         const int e = r + 16 * c;
-        v[c] = e < p.m ? logit_row[e] : 0.0f;
-        if (e >= p.m) taken |= 1u << c;
+        v[c] = e < p.m ? logit_row[e] : none;
     }
     float my_v = 0.0f;
     int my_i = 0;
     for (int j = 0; j < n_pick; ++j) {
-        float bv = 0.0f;
-        int bi = 0x7fffffff;
+        float bv = v[0];
+        int bc = 0;
 #pragma unroll
-        for (int c = 0; c < 16; ++c) {
-            if (taken & (1u << c)) continue;
-            if (bi == 0x7fffffff || v[c] > bv) { bv = v[c]; bi = r + 16 * c; }
-        }
-        better(bv, bi, dpp_f<0x121>(bv), dpp_i<0x121>(bi));
-        better(bv, bi, dpp_f<0x122>(bv), dpp_i<0x122>(bi));
-        better(bv, bi, dpp_f<0x124>(bv), dpp_i<0x124>(bi));
-        better(bv, bi, dpp_f<0x128>(bv), dpp_i<0x128>(bi));
-        if ((bi & 15) == r) taken |= 1u << (bi >> 4);
+        for (int c = 1; c < NC; ++c)
+            if (v[c] > bv) { bv = v[c]; bc = c; }
+        int bi = r + 16 * bc;
+        better_of_two(bv, bi, dpp_f<0x121>(bv), dpp_i<0x121>(bi));
+        better_of_two(bv, bi, dpp_f<0x122>(bv), dpp_i<0x122>(bi));
+        better_of_two(bv, bi, dpp_f<0x124>(bv), dpp_i<0x124>(bi));
+        better_of_two(bv, bi, dpp_f<0x128>(bv), dpp_i<0x128>(bi));
+        const int wc = (bi & 15) == r ? (bi >> 4) : -1;     // the winner leaves its lane's candidates
+#pragma unroll
+        for (int c = 0; c < NC; ++c)
+            if (c == wc) v[c] = none;
         if (r == j) { my_v = bv; my_i = bi; }
     }
     const float top = __shfl(my_v, lane & ~15);
@@ -439,15 +451,15 @@ __device__ __forceinline__ void wait_vmcnt_at_most(int n)
     else __builtin_amdgcn_s_waitcnt(0x0F70);
 }
 
-template <int TG, int NTH, int KB, int MT>
-__global__ void __launch_bounds__(TG * 128) gate_tiled_kernel(GateArgs p)
+template <int TG, int NTH, int KB, int MT, int EG>
+__global__ void __launch_bounds__((TG / MT) * EG * 64) gate_tiled_kernel(GateArgs p)
 {
-    // A wave multiplies MT token tiles (16 tokens each) by NTH expert tiles: its 2 TG / (TG / MT) = 2 MT
-    // expert groups partition the experts.  MT = 2 halves the B fragments read from LDS per MFMA.
+    // A wave multiplies MT token tiles (16 tokens each) by NTH expert tiles: TG / MT groups of token tiles x
+    // EG groups of NTH expert tiles (EG NTH >= expert tiles).  MT = 2 halves the B fragments read from LDS per MFMA.
     static_assert(TG % MT == 0, "token tiles per wave");
     // KB = k elements per stage: 64 (rows of 128 bytes, whole cache lines: what bounds this kernel is the number
     // of line requests a CU keeps in flight, not bytes) where three such stages fit the LDS, else 32
-    constexpr int NWV = 2 * TG;
+    constexpr int NWV = (TG / MT) * EG;                 // waves: token-tile groups x expert groups
     constexpr int RB = KB * 2, CPR = RB / 16, WR = 256 / RB, RPL = 1024 / RB, NSL = KB / 32;
     const int NST = p.n_stage;                          // LDS stages: as many as fit, at most 8
     extern __shared__ __attribute__((aligned(16))) char gsm[];
@@ -460,7 +472,7 @@ __global__ void __launch_bounds__(TG * 128) gate_tiled_kernel(GateArgs p)
     const int rows = w_rows + 16 * TG;
     const int groups = rows / RPL;                      // RPL rows (1 KiB) per wave-wide load
     const int stage_bytes = rows * RB;
-    for (int i = tid; i < p.m_pad; i += TG * 128) hist[i] = 0;
+    for (int i = tid; i < p.m_pad; i += NWV * 64) hist[i] = 0;
 
     // loader: wave w moves row groups w, w+NWV, ...; lane -> row lane/CPR, 16-byte slot lane%CPR holding
     // chunk (lane%CPR) ^ ((row/WR)&(CPR-1))  (conflict-free ds_read_b128 on the 64-bank LDS)
@@ -580,7 +592,11 @@ __global__ void __launch_bounds__(TG * 128) gate_tiled_kernel(GateArgs p)
         for (int tok = wave * 4; tok < 16 * TG; tok += NWV * 4) {
             const int tl = tok + (lane >> 4);
             const bool valid = t0 + tl < p.T;
-            topk_rows(p, logit, valid ? tl : tok, t0 + tl, valid && t0 + tok < p.T, lane, hist);
+            const int tls = valid ? tl : tok;
+            const bool ok = valid && t0 + tok < p.T;
+            if (n_tiles <= 4) topk_rows<4>(p, logit, tls, t0 + tl, ok, lane, hist);
+            else if (n_tiles <= 8) topk_rows<8>(p, logit, tls, t0 + tl, ok, lane, hist);
+            else topk_rows<16>(p, logit, tls, t0 + tl, ok, lane, hist);
         }
     } else {
         for (int tok = wave; tok < 16 * TG; tok += NWV) {
@@ -589,7 +605,7 @@ __global__ void __launch_bounds__(TG * 128) gate_tiled_kernel(GateArgs p)
         }
     }
     __syncthreads();
-    for (int i = tid; i < p.m; i += TG * 128)
+    for (int i = tid; i < p.m; i += NWV * 64)
         if (hist[i] > 0) atomicAdd(&p.expert_cnt[i], hist[i]);
 }
 
@@ -862,14 +878,14 @@ __global__ void __launch_bounds__(1024) route_small_kernel(RowArgs p)
 constexpr int kGateLds = 160 * 1024;                    // LDS of one CU (the tiled gate also holds a 1 KiB histogram)
 
 #define BMOE_GATE_TILED_ALL(X) \
-    X(4, 2, 64, 1) X(4, 2, 32, 1) X(4, 4, 64, 1) X(4, 4, 32, 1) X(4, 4, 32, 2) \
-    X(2, 2, 64, 1) X(2, 2, 32, 1) X(2, 4, 64, 1) X(2, 4, 32, 1) X(2, 4, 32, 2)
+    X(4, 2, 64, 1, 2) X(4, 2, 32, 1, 2) X(4, 4, 64, 1, 2) X(4, 1, 32, 2, 8) X(4, 2, 32, 2, 8) \
+    X(2, 2, 64, 1, 2) X(2, 2, 32, 1, 2) X(2, 1, 64, 2, 8) X(2, 4, 32, 1, 2) X(2, 2, 32, 2, 8)
 
 hipError_t init_route_kernels()
 {
     hipError_t e;
-#define BMOE_SET(TG_, NTH_, KB_, MT_)                                                                    \
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(gate_tiled_kernel<TG_, NTH_, KB_, MT_>),       \
+#define BMOE_SET(TG_, NTH_, KB_, MT_, EG_)                                                                  \
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(gate_tiled_kernel<TG_, NTH_, KB_, MT_, EG_>),  \
                             hipFuncAttributeMaxDynamicSharedMemorySize, kGateLds - 1024);                \
     if (e != hipSuccess) return e;
     BMOE_GATE_TILED_ALL(BMOE_SET)
@@ -938,18 +954,21 @@ hipError_t launch_route(const Dims& D, const bf16_t* x, const void* gate, const 
             g.n_stage = std::max(3, std::min(8, (kGateLds - 1024) / stage));
             const int lds = std::max(g.n_stage * stage, 16 * tgw * D.m_pad * 4);
             const int blocks = ceil_div(D.T, 16 * tgw);
-#define BMOE_GATE_TILED(TG_, NTH_, KB_, MT_) gate_tiled_kernel<TG_, NTH_, KB_, MT_><<<blocks, TG_ * 128, lds, s>>>(g)
-            // more than 8 expert tiles (at most 16): two token tiles per wave and a quarter of the experts
-            // instead of one token tile and half of the experts
-            static_assert(kMaxExperts <= 256, "a wave holds at most four expert tiles per quarter");
+#define BMOE_GATE_TILED(TG_, NTH_, KB_, MT_, EG_) \
+    gate_tiled_kernel<TG_, NTH_, KB_, MT_, EG_><<<blocks, (TG_ / MT_) * EG_ * 64, lds, s>>>(g)
+            // Wave layouts, each measured against its neighbours (more, smaller waves win: the loop is bound by
+            // the latency of its LDS reads and barrier, not by bytes).  Up to 4 expert tiles: a wave holds one
+            // token tile and half of the experts.  Up to 8: two token tiles and one expert tile per wave, 8 expert
+            // groups.  Up to 16: two token tiles and two expert tiles, 8 groups.
+            static_assert(kMaxExperts <= 256, "8 expert groups of two tiles cover every expert");
             if (tgw == 4) {
-                if (half_tiles <= 2) { if (wide) BMOE_GATE_TILED(4, 2, 64, 1); else BMOE_GATE_TILED(4, 2, 32, 1); }
-                else if (half_tiles <= 4) { if (wide) BMOE_GATE_TILED(4, 4, 64, 1); else BMOE_GATE_TILED(4, 4, 32, 1); }
-                else BMOE_GATE_TILED(4, 4, 32, 2);
+                if (half_tiles <= 2) { if (wide) BMOE_GATE_TILED(4, 2, 64, 1, 2); else BMOE_GATE_TILED(4, 2, 32, 1, 2); }
+                else if (half_tiles <= 4) { if (wide) BMOE_GATE_TILED(4, 4, 64, 1, 2); else BMOE_GATE_TILED(4, 1, 32, 2, 8); }
+                else BMOE_GATE_TILED(4, 2, 32, 2, 8);
             } else {
-                if (half_tiles <= 2) { if (wide) BMOE_GATE_TILED(2, 2, 64, 1); else BMOE_GATE_TILED(2, 2, 32, 1); }
-                else if (half_tiles <= 4) { if (wide) BMOE_GATE_TILED(2, 4, 64, 1); else BMOE_GATE_TILED(2, 4, 32, 1); }
-                else BMOE_GATE_TILED(2, 4, 32, 2);
+                if (half_tiles <= 2) { if (wide) BMOE_GATE_TILED(2, 2, 64, 1, 2); else BMOE_GATE_TILED(2, 2, 32, 1, 2); }
+                else if (half_tiles <= 4) { if (wide) BMOE_GATE_TILED(2, 1, 64, 2, 8); else BMOE_GATE_TILED(2, 4, 32, 1, 2); }
+                else BMOE_GATE_TILED(2, 2, 32, 2, 8);
             }
 #undef BMOE_GATE_TILED
         } else {

@@ -45,6 +45,12 @@ SMALL = {
                            [0.5]),
     "tiled_gate_4groups": (WL.LayerConfig("tiled_gate_4groups", T=12500, d=64, F=64, m=60, K=3, way=8, score_fn=1),
                            [1.0, 0.3]),
+    # more than 128 experts in blocks of 32 tokens (wave layout: two token tiles x two expert tiles, 8 groups)
+    "tiled_gate_200_experts": (WL.LayerConfig("tiled_gate_200_experts", T=6200, d=64, F=64, m=200, K=8, way=8,
+                                              zipf_s=1.0), [0.5]),
+    # 128 experts in blocks of 64 tokens (narrow k stages, 8 expert groups of one tile)
+    "tiled_gate_128_experts": (WL.LayerConfig("tiled_gate_128_experts", T=12400, d=64, F=64, m=128, K=6, way=8,
+                                              score_fn=1), [0.4]),
     "mid_tile": (WL.LayerConfig("mid_tile", T=600, d=128, F=256, m=8, K=2, way=4), [1.0, 0.5]),
     "multi_tile": (WL.LayerConfig("multi_tile", T=1500, d=256, F=384, m=4, K=2, way=4, zipf_s=1.2), [1.0, 0.7]),
     # 256-row tiles with long K: the persistent GEMM cuts the tiles left over after its last full round of one
