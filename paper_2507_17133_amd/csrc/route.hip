@@ -1,7 +1,8 @@
 // Routing kernels of the BrownoutMoE layer for gfx950:
 //   prep     clear the expert counters (large batches), split fp32 gate weights into three bf16 pieces
 //            (also the one-time repack behind moe_pack_gate)
-//   gate     affinities s = x.e_i on MFMA (bf16 x 3-piece weights, fp64 running sums) or, for at most 16
+//   gate     affinities s = x.e_i on MFMA (bf16 x 3-piece weights, fp64 running sums; from 32 experts on with
+//            the pieces and the x rows staged in LDS, blocks of 16, 32 or 64 tokens) or, for at most 16
 //            experts and small batches, in plain fp64; TopK by wavefront shuffles, weights g, expert
 //            histogram                                               (Architecture of BrownoutMoE)
 //   count    Algorithm 1's S1/S2 split and unit map (every block, from the counts) and the rows
@@ -605,8 +606,9 @@ __global__ void __launch_bounds__((TG / MT) * EG * 64) gate_tiled_kernel(GateArg
         }
     }
     __syncthreads();
-    for (int i = tid; i < p.m; i += NWV * 64)
-        if (hist[i] > 0) atomicAdd(&p.expert_cnt[i], hist[i]);
+    if (p.expert_cnt != nullptr)                        // small batches: the routing block counts the experts itself
+        for (int i = tid; i < p.m; i += NWV * 64)
+            if (hist[i] > 0) atomicAdd(&p.expert_cnt[i], hist[i]);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -879,7 +881,8 @@ constexpr int kGateLds = 160 * 1024;                    // LDS of one CU (the ti
 
 #define BMOE_GATE_TILED_ALL(X) \
     X(4, 2, 64, 1, 2) X(4, 2, 32, 1, 2) X(4, 4, 64, 1, 2) X(4, 1, 32, 2, 8) X(4, 2, 32, 2, 8) \
-    X(2, 2, 64, 1, 2) X(2, 2, 32, 1, 2) X(2, 1, 64, 2, 8) X(2, 4, 32, 1, 2) X(2, 2, 32, 2, 8)
+    X(2, 2, 64, 1, 2) X(2, 2, 32, 1, 2) X(2, 1, 64, 2, 8) X(2, 4, 32, 1, 2) X(2, 2, 32, 2, 8) \
+    X(1, 1, 64, 1, 8) X(1, 2, 32, 1, 8) X(1, 1, 64, 1, 4)
 
 hipError_t init_route_kernels()
 {
@@ -937,17 +940,16 @@ hipError_t launch_route(const Dims& D, const bf16_t* x, const void* gate, const 
         const int n_tiles = D.m_pad / 16;
         g.NG = n_tiles < 4 ? n_tiles : 4;
         g.KS = std::max(1, std::min(16 / g.NG, 256 / D.m_pad));
-        const int ntw = ceil_div(n_tiles, g.NG);
         g.topk_idx = R.topk_idx; g.topk_w = R.topk_w; g.near_tie = R.near_tie;
         g.expert_cnt = small ? nullptr : R.expert_cnt;
-        // many experts and enough tokens to fill the CUs with wider token tiles: LDS-staged variant
         const int half_tiles = ceil_div(n_tiles, 2);
-        const int tgw = D.T >= 64 * 192 ? 4 : (D.T >= 32 * 192 ? 2 : 0);
+        // 32 experts and more: LDS-staged variant, with wider token tiles once the batch fills the CUs with them
+        const int tgw = n_tiles < 2 ? 0 : (n_tiles >= 4 && D.T >= 64 * 192 ? 4 : (n_tiles >= 4 && D.T >= 32 * 192 ? 2 : 1));
         if (few) {
             const float* gw = static_cast<const float*>(gate);      // fp32 rows in either gate format
             if (D.m <= 8) gate_small_kernel<8, 1><<<D.T, 256, 0, s>>>(g, gw);
             else gate_small_kernel<16, 1><<<D.T, 256, 0, s>>>(g, gw);
-        } else if (n_tiles >= 4 && tgw != 0) {
+        } else if (tgw != 0) {
             const int rows = 3 * D.m_pad + 16 * tgw;
             const bool wide = D.m_pad <= 128 && 3 * rows * 128 <= kGateLds - 1024;    // 64-wide k stages fit
             const int stage = rows * (wide ? 128 : 64);
@@ -961,7 +963,11 @@ hipError_t launch_route(const Dims& D, const bf16_t* x, const void* gate, const 
             // token tile and half of the experts.  Up to 8: two token tiles and one expert tile per wave, 8 expert
             // groups.  Up to 16: two token tiles and two expert tiles, 8 groups.
             static_assert(kMaxExperts <= 256, "8 expert groups of two tiles cover every expert");
-            if (tgw == 4) {
+            if (tgw == 1) {
+                if (n_tiles <= 4) BMOE_GATE_TILED(1, 1, 64, 1, 4);
+                else if (n_tiles <= 8) BMOE_GATE_TILED(1, 1, 64, 1, 8);      // (wide stages always fit here)
+                else BMOE_GATE_TILED(1, 2, 32, 1, 8);
+            } else if (tgw == 4) {
                 if (half_tiles <= 2) { if (wide) BMOE_GATE_TILED(4, 2, 64, 1, 2); else BMOE_GATE_TILED(4, 2, 32, 1, 2); }
                 else if (half_tiles <= 4) { if (wide) BMOE_GATE_TILED(4, 4, 64, 1, 2); else BMOE_GATE_TILED(4, 1, 32, 2, 8); }
                 else BMOE_GATE_TILED(4, 2, 32, 2, 8);
@@ -972,10 +978,8 @@ hipError_t launch_route(const Dims& D, const bf16_t* x, const void* gate, const 
             }
 #undef BMOE_GATE_TILED
         } else {
-            const int blocks = ceil_div(D.T, 16);
-            if (ntw == 1) gate_topk_kernel<1><<<blocks, 1024, 0, s>>>(g);
-            else if (ntw == 2) gate_topk_kernel<2><<<blocks, 1024, 0, s>>>(g);
-            else gate_topk_kernel<4><<<blocks, 1024, 0, s>>>(g);
+            // 17 .. 31 experts never get here (m_pad = 32); at most 16 experts beyond kFewExpertsTokens tokens do
+            gate_topk_kernel<1><<<ceil_div(D.T, 16), 1024, 0, s>>>(g);
         }
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }

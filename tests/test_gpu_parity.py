@@ -245,10 +245,12 @@ def test_forward_replays_from_a_hip_graph(name):
         torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("name", ["tiny", "many_experts", "tiled_gate_2groups"])
+@pytest.mark.parametrize("name", ["tiny", "few_experts_2049_tokens", "sixty_experts_way8", "many_experts",
+                                  "tiled_gate_2groups", "tiled_gate_200_experts", "max_topk_max_shared"])
 def test_exact_ties_go_to_the_lower_expert_id(name):
     """All-zero activations: every affinity is exactly equal, so TopK must list experts 0..K-1 for every token
-    (lower id wins, in all three gate kernels' paths), every token is flagged as a near tie, the weights are
+    (lower id wins: in the fp64 gate, the MFMA gate for few experts, the LDS-staged gate with 4, 8 and 16
+    candidate registers per lane and with one token per wavefront), every token is flagged as a near tie, the weights are
     1/K, and the layer output is zero (FFN(0) = 0)."""
     cfg, _ = SMALL[name]
     L, Lg = _layer(cfg)
