@@ -57,16 +57,13 @@ __global__ void __launch_bounds__(256) prep_kernel(const float* __restrict__ gat
 }
 
 // ------------------------------------------------------------------------------------------------
-// gate: one block = 16 tokens x all experts.  Sixteen wavefronts share the (expert tile, k slice) space:
-// NG = min(4, m_pad/16) expert groups of NTW 16-wide tiles, KS k slices (as many as 16/NG and the
-// 256 partial sums per token of the LDS exchange allow): a wave's bandwidth is bounded by the few loads
-// it keeps in flight, so short slices in many waves are what makes a small batch fast.  Each 64-wide k chunk is
-// accumulated from zero by six 16x16x32 bf16 MFMAs (lo, mid, hi pieces) and folded into an fp64 running
-// sum, which keeps the logit within a few 1e-8 of the exact dot product whatever d is.
+// gate: affinities on MFMA.  Each k chunk is accumulated from zero by 16x16x32 bf16 MFMAs over the low,
+// middle and high piece of the gate weights and folded into an fp64 running sum at least every 64 k, which
+// keeps the logit within a few 1e-8 of the exact dot product whatever d is.
 // ------------------------------------------------------------------------------------------------
 struct GateArgs {
     const bf16_t* x; const unsigned short* split; const float* bias;
-    int T, d, m, m_pad, K, score_fn, NG, KS, n_stage;
+    int T, d, m, m_pad, K, score_fn, n_stage;
     int32_t* topk_idx; float* topk_w; uint8_t* near_tie;
     int32_t* expert_cnt;   // the launch's expert counts, cleared beforehand (atomics); null for small batches,
                            // whose routing block counts the experts itself
@@ -217,126 +214,98 @@ __device__ __forceinline__ void topk_rows(const GateArgs& p, const float* logit,
     }
 }
 
-template <int NTW>
-__global__ void __launch_bounds__(1024) gate_topk_kernel(GateArgs p)
+// gate for at most 16 experts in batches beyond kFewExpertsTokens tokens: one block = 16 tokens x the one tile of
+// experts, 8 wavefronts that split K.  A stage is 256 k: the 48 rows of the three gate pieces and the 16 x rows,
+// as four pieces of 64 k (rows of 128 bytes = whole lines, brought in by direct global->LDS loads, 8 rows per
+// wave instruction; a wave that lets every lane fetch its own 16-byte fragment instead spends its time on tag
+// look-ups: 16 rows x 64 bytes per instruction).  Wave w multiplies the 32-wide half w&1 of piece w>>1 of every
+// stage, three MFMAs (low, middle, high piece) folded into fp64 sums; the eight partial sums of a logit are added
+// in wave order through LDS.  Three stages: two in flight while one is multiplied.
+__global__ void __launch_bounds__(512) gate_few_kernel(GateArgs p)
 {
-    __shared__ double part[16 * kMaxExperts];   // [ks][token][m_pad], KS*m_pad <= 256
-    __shared__ float logit[16 * kMaxExperts];   // [token][m_pad]
-    __shared__ int hist[kMaxExperts];
-
+    constexpr int RB = 128, SUB = 64 * RB, STAGE = 4 * SUB, NST = 3;
+    extern __shared__ __attribute__((aligned(16))) char gsm[];
+    __shared__ int hist[16];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);
     const int t0 = blockIdx.x * 16;
-    const int n_tiles = p.m_pad >> 4;
-    for (int i = tid; i < p.m_pad; i += 1024) hist[i] = 0;
+    if (tid < 16) hist[tid] = 0;
+    const int n_sub = p.d >> 6, n_stage = (n_sub + 3) >> 2;
+    const int sub = wave_s >> 1, sl = wave_s & 1;
 
-    const bool active = wave < p.NG * p.KS;
-    const int ng = wave % p.NG, ks = wave / p.NG;
-    if (active) {
-        const int ksteps = p.d >> 5;
-        const int per = (ksteps + p.KS - 1) / p.KS;
-        const int k_lo = ks * per, k_hi = min(ksteps, k_lo + per);
-        const int trow = min(t0 + (lane & 15), p.T - 1);
-        const bf16_t* ap = p.x + (size_t)trow * p.d + 8 * (lane >> 4);
-        const size_t piece = (size_t)p.m_pad * p.d;
-        const unsigned short* bp[NTW];
-        bool tile_ok[NTW];
+    // loader: the four loads of wave w bring rows 8 (4 (w&1) + i) .. +7 of piece w>>1; 16-byte chunk c of row r
+    // sits in slot c ^ ((r/2)&7) (conflict-free ds_read_b128)
+    const unsigned short* srcp[4];
 #pragma unroll
-        for (int nt = 0; nt < NTW; ++nt) {
-            const int tile = ng * NTW + nt;
-            tile_ok[nt] = tile < n_tiles;
-            const int erow = (tile_ok[nt] ? tile : 0) * 16 + (lane & 15);
-            bp[nt] = p.split + (size_t)erow * p.d + 8 * (lane >> 4);
-        }
-        double sum[NTW][4];
-        f32x4 acc[NTW];
-#pragma unroll
-        for (int nt = 0; nt < NTW; ++nt) {
-            acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int v = 0; v < 4; ++v) sum[nt][v] = 0.0;
-        }
-        // UNR k steps per round trip: all their fragments are requested before the first MFMA, so a wave
-        // pays the memory latency once per UNR*32 k instead of once per 32
-        constexpr int UNR = NTW == 1 ? 8 : (NTW == 2 ? 4 : 2);
-        int kstep = k_lo;
-        for (; kstep + UNR <= k_hi; kstep += UNR) {
-            bf16x8 a[UNR], b[UNR][NTW][3];
-#pragma unroll
-            for (int u = 0; u < UNR; ++u) {
-                const int ko = (kstep + u) << 5;
-                a[u] = *reinterpret_cast<const bf16x8*>(ap + ko);
-#pragma unroll
-                for (int nt = 0; nt < NTW; ++nt) {
-#pragma unroll
-                    for (int pz = 0; pz < 3; ++pz)
-                        b[u][nt][pz] = *reinterpret_cast<const bf16x8*>(bp[nt] + pz * piece + ko);
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < UNR; ++u) {
-#pragma unroll
-                for (int nt = 0; nt < NTW; ++nt) {
-                    acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u], b[u][nt][2], acc[nt], 0, 0, 0);
-                    acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u], b[u][nt][1], acc[nt], 0, 0, 0);
-                    acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u], b[u][nt][0], acc[nt], 0, 0, 0);
-                }
-                if (u & 1) {
-#pragma unroll
-                    for (int nt = 0; nt < NTW; ++nt) {
-#pragma unroll
-                        for (int v = 0; v < 4; ++v) sum[nt][v] += (double)acc[nt][v];
-                        acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-                    }
-                }
-            }
-        }
-        for (; kstep < k_hi; ++kstep) {
-            const int ko = kstep << 5;
-            const bf16x8 a = *reinterpret_cast<const bf16x8*>(ap + ko);
-#pragma unroll
-            for (int nt = 0; nt < NTW; ++nt) {
-                const bf16x8 b_lo = *reinterpret_cast<const bf16x8*>(bp[nt] + 2 * piece + ko);
-                const bf16x8 b_mid = *reinterpret_cast<const bf16x8*>(bp[nt] + piece + ko);
-                const bf16x8 b_hi = *reinterpret_cast<const bf16x8*>(bp[nt] + ko);
-                acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_lo, acc[nt], 0, 0, 0);
-                acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_mid, acc[nt], 0, 0, 0);
-                acc[nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_hi, acc[nt], 0, 0, 0);
-            }
-#pragma unroll
-            for (int nt = 0; nt < NTW; ++nt) {
-#pragma unroll
-                for (int v = 0; v < 4; ++v) sum[nt][v] += (double)acc[nt][v];
-                acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-            }
-        }
-        // MFMA 16x16 result layout: lane holds column (lane&15) = expert, rows 4*(lane>>4)+v = tokens.
-#pragma unroll
-        for (int nt = 0; nt < NTW; ++nt) {
-            if (!tile_ok[nt]) continue;
-            const int e = (ng * NTW + nt) * 16 + (lane & 15);
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int tok = 4 * (lane >> 4) + v;
-                part[(ks * 16 + tok) * p.m_pad + e] = sum[nt][v];
-            }
-        }
+    for (int i = 0; i < 4; ++i) {
+        const int row = (sl * 4 + i) * 8 + (lane >> 3);
+        const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+        const unsigned short* src = row < 48 ? p.split + (size_t)row * p.d
+                                             : reinterpret_cast<const unsigned short*>(p.x) +
+                                                   (size_t)min(t0 + row - 48, p.T - 1) * p.d;
+        srcp[i] = src + chunk * 8;
     }
+    auto issue = [&](int st, int buf) {
+        const int piece = min(st * 4 + sub, n_sub - 1);   // past the end of K: the last piece again, never multiplied
+        char* dst = gsm + buf * STAGE + sub * SUB + sl * 4096;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(srcp[i] + piece * 64),
+                                             (__attribute__((address_space(3))) void*)(dst + i * 1024), 16, 0, 0);
+    };
+    // fragment of row (base + lane&15), 32-wide half sl: chunks 4 sl + (lane>>4); bases are multiples of 16 rows
+    const int coff = ((sl * 4 + (lane >> 4)) ^ (((lane & 15) >> 1) & 7)) << 4;
+    const int roff = (lane & 15) * RB + coff;
+    double sum[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int q = 0; q < NST - 1; ++q)
+        if (q < n_stage) issue(q, q);
+    int buf = 0;
+    for (int st = 0; st < n_stage; ++st) {
+        // loads complete in order: stage st has landed once only the four loads of stage st+1 are outstanding
+        if (st + 1 < n_stage) __builtin_amdgcn_s_waitcnt(0x0F74);
+        else __builtin_amdgcn_s_waitcnt(0x0F70);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();                     // stage st is in LDS for everyone; stage st-1 is free
+        asm volatile("" ::: "memory");
+        if (st + NST - 1 < n_stage) issue(st + NST - 1, buf == 0 ? NST - 1 : buf - 1);
+        if (st * 4 + sub < n_sub) {
+            const char* St = gsm + buf * STAGE + sub * SUB + roff;
+            const bf16x8 a = *reinterpret_cast<const bf16x8*>(St + 48 * RB);
+            const bf16x8 b_hi = *reinterpret_cast<const bf16x8*>(St);
+            const bf16x8 b_mid = *reinterpret_cast<const bf16x8*>(St + 16 * RB);
+            const bf16x8 b_lo = *reinterpret_cast<const bf16x8*>(St + 32 * RB);
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_lo, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_mid, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b_hi, acc, 0, 0, 0);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) sum[v] += (double)acc[v];
+        }
+        buf = buf + 1 == NST ? 0 : buf + 1;
+    }
+    __syncthreads();                                      // every wave is done with the stages: reuse them
+    double* part = reinterpret_cast<double*>(gsm);        // [wave][token][expert]
+    float* logit = reinterpret_cast<float*>(gsm + 8 * 256 * 8);
+    // MFMA 16x16 result layout: lane holds column (lane&15) = expert, rows 4*(lane>>4)+v = tokens
+#pragma unroll
+    for (int v = 0; v < 4; ++v) part[(wave * 16 + 4 * (lane >> 4) + v) * 16 + (lane & 15)] = sum[v];
     __syncthreads();
-    for (int i = tid; i < 16 * p.m_pad; i += 1024) {
-        const int tok = i / p.m_pad, e = i - tok * p.m_pad;
+    if (tid < 256) {
         double s = 0.0;
-        for (int q = 0; q < p.KS; ++q) s += part[(q * 16 + tok) * p.m_pad + e];
+#pragma unroll
+        for (int w = 0; w < 8; ++w) s += part[w * 256 + tid];
+        const int e = tid & 15;
         if (p.bias != nullptr && e < p.m) s += (double)p.bias[e];
-        logit[i] = (float)s;
+        logit[tid] = (float)s;
     }
     __syncthreads();
-
-    // TopK: one token per wavefront
-    if (t0 + wave < p.T) topk_token(p, logit + wave * p.m_pad, t0 + wave, lane, hist);
+    if (wave < 4) {                                       // four tokens per wavefront (K + 1 <= m_pad = 16 picks)
+        const int tl = wave * 4 + (lane >> 4);
+        const bool valid = t0 + tl < p.T;
+        topk_rows<1>(p, logit, valid ? tl : wave * 4, t0 + tl, valid && t0 + wave * 4 < p.T, lane, hist);
+    }
     __syncthreads();
-    if (p.expert_cnt != nullptr)
-        for (int i = tid; i < p.m; i += 1024)
-            if (hist[i] > 0) atomicAdd(&p.expert_cnt[i], hist[i]);
+    if (p.expert_cnt != nullptr && tid < p.m && hist[tid] > 0) atomicAdd(&p.expert_cnt[tid], hist[tid]);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -430,7 +399,7 @@ __global__ void __launch_bounds__(256) gate_small_kernel(GateArgs p, const float
 // (token group tg = wave % TG, expert half eh = wave / TG).  The three weight pieces of a 32-wide k
 // step ([3][m_pad] rows of 64 bytes) are staged in LDS by global_load_lds_dwordx4 (3 stages) and read
 // together with the block's x rows and read by every wave, so the split gate matrix is fetched once per
-// 16*TG tokens instead of once per 16.  Same arithmetic as gate_topk_kernel.
+// 16*TG tokens instead of once per 16.
 // ------------------------------------------------------------------------------------------------
 // s_waitcnt vmcnt(n) for a run-time n (the instruction takes an immediate): waits for at most the largest
 // listed value <= n, which is never too lax.
@@ -877,6 +846,7 @@ __global__ void __launch_bounds__(1024) route_small_kernel(RowArgs p)
     if (t < p.T) scatter_token(p, unit_s, bm + (size_t)wave * p.U, off_s, segoff + wave * p.U, t, lane);
 }
 
+constexpr int kGateFewLds = 3 * 4 * 64 * 128;          // three stages of four 64-row pieces (gate_few_kernel)
 constexpr int kGateLds = 160 * 1024;                    // LDS of one CU (the tiled gate also holds a 1 KiB histogram)
 
 #define BMOE_GATE_TILED_ALL(X) \
@@ -893,6 +863,9 @@ hipError_t init_route_kernels()
     if (e != hipSuccess) return e;
     BMOE_GATE_TILED_ALL(BMOE_SET)
 #undef BMOE_SET
+    e = hipFuncSetAttribute(reinterpret_cast<const void*>(gate_few_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            kGateFewLds);
+    if (e != hipSuccess) return e;
     return hipFuncSetAttribute(reinterpret_cast<const void*>(route_small_kernel),
                                hipFuncAttributeMaxDynamicSharedMemorySize, kSmallSegs * kMaxUnits * 12);
 }
@@ -938,8 +911,6 @@ hipError_t launch_route(const Dims& D, const bf16_t* x, const void* gate, const 
         g.bias = gate_bias;
         g.T = D.T; g.d = D.d; g.m = D.m; g.m_pad = D.m_pad; g.K = D.K; g.score_fn = D.score_fn; g.n_stage = 3;
         const int n_tiles = D.m_pad / 16;
-        g.NG = n_tiles < 4 ? n_tiles : 4;
-        g.KS = std::max(1, std::min(16 / g.NG, 256 / D.m_pad));
         g.topk_idx = R.topk_idx; g.topk_w = R.topk_w; g.near_tie = R.near_tie;
         g.expert_cnt = small ? nullptr : R.expert_cnt;
         const int half_tiles = ceil_div(n_tiles, 2);
@@ -978,8 +949,8 @@ hipError_t launch_route(const Dims& D, const bf16_t* x, const void* gate, const 
             }
 #undef BMOE_GATE_TILED
         } else {
-            // 17 .. 31 experts never get here (m_pad = 32); at most 16 experts beyond kFewExpertsTokens tokens do
-            gate_topk_kernel<1><<<ceil_div(D.T, 16), 1024, 0, s>>>(g);
+            // at most 16 experts beyond kFewExpertsTokens tokens
+            gate_few_kernel<<<ceil_div(D.T, 16), 512, kGateFewLds, s>>>(g);
         }
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
