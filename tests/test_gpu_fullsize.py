@@ -30,6 +30,10 @@ CASES = [
     ("qwen3_30b_a3b", {}, 0.5, 256), ("qwen3_30b_a3b", {}, 0.0, 320),
     # a batch of 1024 tokens over 128 skewed experts: many units with fewer than 16 rows
     ("qwen3_30b_a3b", {"T": 1024}, 0.0, ALL), ("qwen3_30b_a3b", {"T": 1024}, 0.5, ALL),
+    # 4096 tokens over 128 experts: the LDS-staged gate with 16-token blocks on every CU
+    ("qwen3_30b_a3b", {"T": 4096}, 0.25, 256),
+    # 16 384 tokens over 8 experts: the K-splitting gate for few experts, 256 routing segments
+    ("mixtral_prefill", {"T": 16384}, 0.3, 256),
     ("deepseek_v3", {}, 0.4, 256), ("deepseek_v3", {}, 0.0, 560),
     # the paper's 60-expert layer shape at the three (way, threshold) settings of its throughput experiment
     # (Results): (8, 0.4), (4, 0.2), (2, 0), and with every multi-member group on its united expert
