@@ -589,14 +589,24 @@ __device__ __forceinline__ void brownout_decide(const int* cnt_s, unsigned char*
                                                 double threshold, int full, int tid, bool write,
                                                 int32_t* expert_unit, uint8_t* expert_in_s1)
 {
+    // cnt_s: 16-byte aligned, zero from m up to the next multiple of 4 (a count of 0 adds nothing to P or S).
+    // Four counts per LDS read, and sums in 32 bits (the counts add up to T K <= 2^30): the loop is bound by the
+    // latency of its reads.
     bool in_s1 = false;
     if (tid < m) {
         const int c = cnt_s[tid];
-        long long P = 0, S = 0;
-        for (int j = 0; j < m; ++j) {
-            const int cj = cnt_s[j];
-            S += cj;
-            if (cj > c || (cj == c && j < tid)) P += cj;
+        int P = 0, S = 0;
+        const int4* c4 = reinterpret_cast<const int4*>(cnt_s);
+        const int n4 = (m + 3) >> 2;
+#pragma unroll 4
+        for (int q = 0; q < n4; ++q) {
+            const int4 v = c4[q];
+            const int j = 4 * q;
+            S += (v.x + v.y) + (v.z + v.w);
+            P += (v.x > c || (v.x == c && j < tid)) ? v.x : 0;
+            P += (v.y > c || (v.y == c && j + 1 < tid)) ? v.y : 0;
+            P += (v.z > c || (v.z == c && j + 2 < tid)) ? v.z : 0;
+            P += (v.w > c || (v.w == c && j + 3 < tid)) ? v.w : 0;
         }
         in_s1 = (double)P < (double)S * threshold;
         s2_s[tid] = (!in_s1 && c > 0) ? 1 : 0;
@@ -648,12 +658,13 @@ __device__ __forceinline__ void mark_units(const RowArgs& p, const int* unit_s, 
 
 __global__ void __launch_bounds__(256) route_count_kernel(RowArgs p)
 {
-    __shared__ int cnt_s[kMaxExperts];
+    __shared__ __attribute__((aligned(16))) int cnt_s[kMaxExperts];
     __shared__ int unit_s[kMaxExperts];
     __shared__ unsigned char s2_s[kMaxExperts];
     __shared__ unsigned long long bm[4][kMaxUnits];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (tid < p.m) cnt_s[tid] = p.expert_cnt[tid];
+    static_assert(kMaxExperts <= 256 && kMaxExperts % 4 == 0, "one thread per count, counts read four at a time");
+    if (tid < kMaxExperts) cnt_s[tid] = tid < p.m ? p.expert_cnt[tid] : 0;
     for (int i = tid; i < 4 * kMaxUnits; i += 256) (&bm[0][0])[i] = 0ull;
     __syncthreads();
     brownout_decide(cnt_s, s2_s, unit_s, p.m, p.way, p.threshold, p.full, tid, blockIdx.x == 0, p.expert_unit,
@@ -790,7 +801,7 @@ __global__ void __launch_bounds__(256) route_scatter_kernel(RowArgs p)
 __global__ void __launch_bounds__(1024) route_small_kernel(RowArgs p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char rsm[];
-    __shared__ int cnt_s[kMaxExperts];
+    __shared__ __attribute__((aligned(16))) int cnt_s[kMaxExperts];
     __shared__ int unit_s[kMaxExperts];
     __shared__ unsigned char s2_s[kMaxExperts];
     __shared__ int ucnt_s[kMaxUnits];
@@ -799,7 +810,7 @@ __global__ void __launch_bounds__(1024) route_small_kernel(RowArgs p)
     int* segoff = reinterpret_cast<int*>(rsm + (size_t)kSmallSegs * p.U * 8);                  // [16][U]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     // cnt_i (the input of Algorithm 1) straight from the TopK lists: at most 1024 tokens, one thread each
-    if (tid < p.m) cnt_s[tid] = 0;
+    if (tid < kMaxExperts) cnt_s[tid] = 0;
     for (int i = tid; i < kSmallSegs * p.U; i += 1024) bm[i] = 0ull;
     __syncthreads();
     if (tid < p.T)
